@@ -1,0 +1,114 @@
+/*
+ * CPU oracle for the JoT token-finalization pass -- row statistics.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the
+ * GPU library is checked against.  Nothing on the product path may call it;
+ * it shares no code, header, table or helper with the HIP implementation.
+ *
+ * What it computes, per logit row (paper Section 4.1, "Confidence Metric",
+ * Eq. 2 and the first two computations of Algorithm 1):
+ *
+ *     pi   = softmax(l)                 (no temperature)
+ *     p1   = largest entry of pi,  p2 = second largest entry (of the multiset)
+ *     a    = argmax_v pi_v              (smallest index among equal maxima)
+ *
+ * The row is widened exactly to double (fp32 and bf16 are subsets of double)
+ * and everything is evaluated in double, in plain index order:
+ *
+ *     m1 = max_v l_v,  a = first v with l_v = m1,  m2 = max_{v != a} l_v
+ *     S  = sum_v exp(l_v - m1)          =>  p1 = 1/S,  p2 = exp(m2 - m1)/S
+ *
+ * softmax is strictly increasing in the logit, so the top-2 of pi are the
+ * top-2 of l; jot_oracle_softmax_row() returns the whole vector pi so the
+ * tests can check that statement (and sum(pi) = 1) directly.
+ *
+ * Rows that contain NaN or +inf, or whose entries are all -inf, have no
+ * softmax; they are reported with status 1 and S = NaN (the caller must not
+ * finalize them).  -inf entries are ordinary: they contribute exp(-inf) = 0.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+
+static double widen(const void *row, int dtype, int64_t v)
+{
+    if (dtype == ORACLE_F32)
+        return (double)((const float *)row)[v];
+    /* bf16 is the upper half of an IEEE binary32 */
+    uint32_t bits = (uint32_t)((const uint16_t *)row)[v] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+/* One row.  Returns 0 if the row has a softmax, 1 otherwise. */
+static int row_stats(const void *row, int dtype, int32_t V,
+                     int32_t *a, double *m1, double *m2, double *S)
+{
+    int bad = 0;
+    double best = -INFINITY;
+    int32_t arg = 0;
+    for (int32_t v = 0; v < V; v++) {
+        double x = widen(row, dtype, v);
+        if (isnan(x) || x == INFINITY)
+            bad = 1;
+        if (x > best) {          /* strict: the first maximum keeps the index */
+            best = x;
+            arg = v;
+        }
+    }
+    double second = -INFINITY;
+    for (int32_t v = 0; v < V; v++) {
+        if (v == arg)
+            continue;
+        double x = widen(row, dtype, v);
+        if (x > second)
+            second = x;
+    }
+    *a = arg;
+    *m1 = best;
+    *m2 = second;
+    if (bad || best == -INFINITY) {
+        *S = NAN;
+        return 1;
+    }
+    double sum = 0.0;
+    for (int32_t v = 0; v < V; v++)
+        sum += exp(widen(row, dtype, v) - best);
+    *S = sum;
+    return 0;
+}
+
+/*
+ * rows      : n_rows rows, row k starts at element k*row_stride
+ * dtype     : 0 = fp32, 1 = bf16 (stored as uint16)
+ * outputs   : arrays of n_rows; status[k] = 0 ok / 1 no softmax
+ * n_threads : OpenMP threads over rows (<= 0: library default)
+ */
+void jot_oracle_row_stats(const void *rows, int dtype, int64_t n_rows,
+                          int64_t row_stride, int32_t V,
+                          int32_t *a, double *m1, double *m2, double *S,
+                          int32_t *status, int n_threads)
+{
+    const size_t esz = dtype == ORACLE_F32 ? 4 : 2;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads > 0 ? n_threads : 1)
+#endif
+    for (int64_t k = 0; k < n_rows; k++) {
+        const char *row = (const char *)rows + (size_t)k * (size_t)row_stride * esz;
+        status[k] = row_stats(row, dtype, V, &a[k], &m1[k], &m2[k], &S[k]);
+    }
+}
+
+/* Whole probability vector of one row, pi_v = exp(l_v - m1) / S (for tests). */
+int jot_oracle_softmax_row(const void *row, int dtype, int32_t V, double *pi)
+{
+    int32_t a;
+    double m1, m2, S;
+    int st = row_stats(row, dtype, V, &a, &m1, &m2, &S);
+    for (int32_t v = 0; v < V; v++)
+        pi[v] = st ? NAN : exp(widen(row, dtype, v) - m1) / S;
+    return st;
+}
