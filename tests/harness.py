@@ -1,0 +1,78 @@
+"""Lock-step driver shared by the CPU and GPU tests: runs the oracle over a synthetic
+trajectory, keeps every confidence clear of its threshold by adjusting the *input*
+(never the oracle), and hands each step's inputs and expected outputs to the caller.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from gen.configs import JotConfig
+from gen.host import HostGenerator
+from gen.trajectory import Trajectory
+from oracle import jot_oracle as O
+
+GUARD = 1e-4          # |conf - tau| >= GUARD * max(1, |tau|) for every examined position
+MAX_BUMPS = 200
+
+
+def oracle_params(cfg: JotConfig) -> O.OracleParams:
+    return O.OracleParams(B=cfg.B, L=cfg.L, V=cfg.V, dtype=cfg.dtype, conf_mode=cfg.conf_mode,
+                          tau_max=cfg.tau_max, tau_min=cfg.tau_min, gamma=cfg.gamma, D=cfg.D,
+                          eps=cfg.eps, gen_start=cfg.gen_start, block_size=cfg.block_size)
+
+
+def too_close(rec: O.StepRecord) -> np.ndarray:
+    ok = rec.status == 0
+    with np.errstate(invalid="ignore"):
+        near = np.abs(rec.conf - rec.tau) < GUARD * np.maximum(1.0, np.abs(rec.tau))
+    return np.flatnonzero(ok & near)
+
+
+class LockstepRun:
+    def __init__(self, cfg: JotConfig, threads: int = 1, batch_rows=None):
+        """batch_rows: optional list of batch rows b to follow (rows are independent decodes);
+        the oracle then runs on that sub-batch only, positions are reported in the full
+        canvas numbering."""
+        self.cfg = cfg
+        self.traj = Trajectory(cfg)
+        self.gen = HostGenerator(cfg, self.traj.target, self.traj.rival, threads)
+        tokens, masked = self.traj.initial_canvas()
+        self.batch_rows = list(range(cfg.B)) if batch_rows is None else list(batch_rows)
+        sub = cfg.replace(B=len(self.batch_rows))
+        self.state = O.OracleState.init(oracle_params(sub), tokens[self.batch_rows],
+                                        masked[self.batch_rows], threads=threads)
+        self.n_bumps = 0
+
+    def to_full(self, sub_pos: np.ndarray) -> np.ndarray:
+        L = self.cfg.L
+        rows = np.asarray(self.batch_rows, np.int64)
+        return rows[sub_pos // L] * L + sub_pos % L
+
+    def active_full(self) -> np.ndarray:
+        return self.to_full(self.state.active_list())
+
+    def next_step(self):
+        """Advance the oracle one step.  Returns (rec, T, R, rows) where rec.active is in
+        sub-batch numbering, T/R are the final planted tables of this step (full canvas) and
+        rows are the logit rows the oracle saw (a view valid until the next call)."""
+        st, tr = self.state, self.traj
+        n = st.step_index + 1
+        act_full = self.active_full()
+        T, R = tr.planted(n)
+        rows = self.gen.rows(n, act_full, T, R)
+        rec = st.evaluate(rows)
+        for _ in range(MAX_BUMPS):
+            bad = too_close(rec)
+            if bad.size == 0:
+                break
+            for k in bad:
+                tr.bump(n, int(act_full[k]))
+            self.n_bumps += int(bad.size)
+            T, R = tr.planted(n)
+            fixer = HostGenerator(self.cfg, tr.target, tr.rival, 1)
+            rows[bad] = fixer.rows(n, act_full[bad], T, R)
+            rec = st.evaluate(rows)
+        else:
+            raise RuntimeError("could not clear the guard band")
+        st.apply(rec)
+        return rec, T, R, rows
