@@ -1,0 +1,165 @@
+/*
+ * jot.h -- C ABI of the JoT token-finalization pass for AMD Instinct MI355X (gfx950).
+ *
+ * One call to jot_step() performs, for one denoising step n of a masked-diffusion decoder,
+ * what the paper's Algorithm 1 does between "compute logits" and "apply transfer schedule":
+ *
+ *   for every examined (still masked, eligible) position i:
+ *     pi = softmax(l^i) over the vocabulary, no temperature          (Section 4.1, Confidence Metric)
+ *     p1, p2 = two largest probabilities, a = argmax                   (Section 4.1)
+ *     conf  = p1 / (p2 + eps)                                          (Eq. 2)   [or p1, or p1 - p2]
+ *     w     = sum of gamma^|i-j| over resolved j, 1 <= |i-j| <= D      (Eq. 3)
+ *     phi   = min(1, w / w_max), w_max = 2 * sum_{d=1..D} gamma^d      (Eq. 4)
+ *     tau_i = tau_max - (tau_max - tau_min) * phi                      (Eq. 5)
+ *     conf >= tau_i  =>  token[i] = a, position leaves the masked set  (Eq. 6)
+ *   all decisions of a step use the mask as it was when the step began (Algorithm 1: M_n is
+ *   formed once per step); finalization is uncapped; prompt tokens count as resolved context
+ *   and, with semi-autoregressive decoding, only the current block is examined
+ *   (Section 4.2, Implementation details).
+ *
+ * Only the logit rows of examined positions are read.  Frozen positions cost no memory traffic.
+ *
+ * Conventions
+ *   - Every pointer named *_dev is DEVICE memory owned by the caller.  The library never
+ *     allocates or frees device memory; its working memory is the caller's workspace.
+ *   - `stream` is a hipStream_t passed as void*; NULL is the default stream.  jot_init_state()
+ *     and jot_step() only enqueue work on that stream and return; they do not synchronise
+ *     (jot_init_state synchronises once).  A state must always be used with the same stream,
+ *     or the caller must order the streams itself.
+ *   - Return value 0 = success, negative = one of JOT_ERR_*.  Arguments are validated on the
+ *     host before any device work, so a failing call has no effect on the device.
+ *   - Calls on the same state must not overlap (one thread at a time); different states are
+ *     independent.
+ *   - Indices: a canvas position is the flattened index b*L + i, 0 <= b < B, 0 <= i < L.
+ *     Steps are numbered from 1.
+ */
+#ifndef JOT_H
+#define JOT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct jot_state jot_state;      /* opaque, host memory, created by jot_init_state */
+
+typedef enum { JOT_F32 = 0, JOT_BF16 = 1 } jot_dtype;
+
+/* Confidence signal compared with tau_i.  All three come from the same (p1, p2). */
+typedef enum {
+    JOT_CONF_RATIO   = 0,   /* Eq. 2: p1 / (p2 + eps); thresholds on the ratio scale (e.g. 90, 30)   */
+    JOT_CONF_MAXPROB = 1,   /* p1; thresholds in [0, 1]                                                */
+    JOT_CONF_PROBGAP = 2    /* p1 - p2; thresholds in [0, 1]                                           */
+} jot_conf_mode;
+
+enum {
+    JOT_OK                      =  0,
+    JOT_ERR_INVALID_ARG         = -1,
+    JOT_ERR_NULL_POINTER        = -2,
+    JOT_ERR_UNSUPPORTED_DTYPE   = -3,
+    JOT_ERR_WORKSPACE_TOO_SMALL = -4,
+    JOT_ERR_MISALIGNED          = -5,
+    JOT_ERR_HIP                 = -6,
+    JOT_ERR_NO_DEVICE           = -7
+};
+
+typedef struct {
+    int32_t B, L, V;          /* batch rows, canvas length INCLUDING the prompt, vocabulary size (>= 2) */
+    int32_t dtype;            /* jot_dtype of the logits                                                */
+    int32_t conf_mode;        /* jot_conf_mode                                                          */
+    float   tau_max, tau_min; /* Eq. 5; tau_min <= tau_max                                              */
+    float   gamma;            /* Eq. 3 decay, in (0, 1]                                                 */
+    int32_t D;                /* Eq. 3 window radius, 0..32; 0 switches spatial modulation off (phi=0)  */
+    float   eps;              /* Eq. 2; the paper uses 1e-12; >= 0                                      */
+    int32_t gen_start;        /* first generation position (= prompt length), 0..L; blocks count from it*/
+    int32_t block_size;       /* 0: every masked position is examined each step (fully parallel decode);
+                                 >0: only the masked positions of each row's current block, i.e. the
+                                 block [gen_start + k*block_size, gen_start + (k+1)*block_size) that
+                                 holds the row's lowest masked position                                 */
+} jot_params;
+
+/* Bytes of device workspace a state with these parameters needs (multiple of 256).
+ * <0: JOT_ERR_* (invalid parameters).  Host only. */
+int64_t jot_workspace_bytes(const jot_params* p);
+
+/*
+ * Create a state.  Copies the initial canvas into the workspace and builds the first list of
+ * examined positions.  Synchronises `stream` once before returning.
+ *   out            : receives the state (host object; free with jot_release)
+ *   workspace_dev  : device memory, 256-byte aligned, >= jot_workspace_bytes(p) bytes; must stay
+ *                    valid and untouched by the caller for the life of the state
+ *   tokens_dev     : [B, L] int32, row-major; tokens of resolved positions (value at a masked
+ *                    position is ignored and later overwritten by the finalized token)
+ *   masked_dev     : [B, L] uint8, 1 = masked ([M]), 0 = resolved (prompt or already decoded)
+ */
+int jot_init_state(jot_state** out, const jot_params* p,
+                   void* workspace_dev, int64_t workspace_bytes,
+                   const int32_t* tokens_dev, const uint8_t* masked_dev, void* stream);
+
+/*
+ * One finalization pass (step n = number of jot_step calls so far on this state, from 1).
+ *   logits_dev : logits of the whole canvas, element (b, i, v) at
+ *                logits_dev[b*stride_b + i*stride_l + v]; strides in ELEMENTS; V contiguous.
+ *                Must be 16-byte aligned, and stride_b, stride_l must keep every row 16-byte
+ *                aligned.  Read-only; only rows of examined positions are touched, so rows of
+ *                frozen positions need not hold valid data.
+ *   -inf logits are allowed (probability 0).  A row holding NaN or +inf, or only -inf, has no
+ *   softmax: the position is left masked and counted by jot_anomaly_count().
+ * Asynchronous: returns after enqueueing on `stream`.  With no examined position left it is a
+ * no-op on the canvas (Algorithm 1 would have left the loop).
+ */
+int jot_step(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l, void* stream);
+
+/* Number of positions the NEXT step would examine (0 = decoding finished).  Waits for the work
+ * enqueued so far on this state.  <0: JOT_ERR_*. */
+int64_t jot_active_count(jot_state* s);
+
+/* Number of jot_step calls so far (host counter, no synchronisation). */
+int32_t jot_step_index(const jot_state* s);
+
+/* Rows skipped so far because they had no softmax.  Waits like jot_active_count. */
+int64_t jot_anomaly_count(jot_state* s);
+
+/*
+ * Device views into the workspace.  Pointers stay valid until the workspace is freed; the
+ * contents are those of the last enqueued step once its stream work has completed.
+ */
+const int32_t* jot_tokens(const jot_state* s);        /* [B, L] current canvas                        */
+const uint8_t* jot_masked(const jot_state* s);        /* [B, L] 1 = still masked                      */
+const int32_t* jot_commit_step(const jot_state* s);   /* [B, L] step at which finalized, 0 = not (yet) */
+const int32_t* jot_active_list(const jot_state* s);   /* [jot_active_count] ascending b*L+i, next step */
+/* Finalizations in order: triples (step, b*L+i, token), steps non-decreasing, positions
+ * ascending within a step.  *n receives the number of triples (waits like jot_active_count). */
+const int32_t* jot_commit_log(jot_state* s, int64_t* n);
+
+/*
+ * Per-position results of the LAST step, aligned with the list that step examined
+ * (jot_examined_list, length *n = number of examined positions; waits like jot_active_count):
+ * token = argmax, conf, p1, p2, tau = tau_i.  For rows without a softmax conf is NaN.
+ */
+const int32_t* jot_examined_list(jot_state* s, int64_t* n);
+const int32_t* jot_last_token(const jot_state* s);
+const float*   jot_last_conf(const jot_state* s);
+const float*   jot_last_p1(const jot_state* s);
+const float*   jot_last_p2(const jot_state* s);
+const float*   jot_last_tau(const jot_state* s);
+
+/*
+ * Optional timing of the vocabulary-reduction kernel (the one that reads the logits):
+ * when enabled, jot_step brackets that kernel with HIP events on `stream`.
+ * jot_profile_read waits for the last step and returns the kernel's duration of that step in
+ * milliseconds in *vocab_reduce_ms.
+ */
+int jot_profile_enable(jot_state* s, int on);
+int jot_profile_read(jot_state* s, float* vocab_reduce_ms);
+
+/* Free the host object and its pinned host counters (device memory is the caller's). */
+void jot_release(jot_state* s);
+
+const char* jot_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JOT_H */

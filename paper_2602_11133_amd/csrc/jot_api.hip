@@ -1,0 +1,379 @@
+// Host side of the C ABI declared in include/jot.h: argument validation, workspace layout and
+// the per-step launch sequence.  No device memory is allocated here; the only host resources
+// are the state object, one small pinned buffer for counter read-back and a few events.
+#include "../../include/jot.h"
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <new>
+#include <stdlib.h>
+#include <string.h>
+
+#include "jot_compact.h"
+#include "jot_decide.h"
+#include "jot_device.h"
+#include "jot_vocab_reduce.h"
+
+namespace {
+
+constexpr int64_t kAlign = 256;
+
+inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// Persistent grid of the vocabulary reduction: workgroups per compute unit, and how many work
+// items a step aims for (rows are split into pieces when fewer rows than that are examined).
+constexpr int kWgPerCu = 8;
+constexpr int kFallbackCus = 256;
+constexpr int kItemsPerWg = 4;
+
+struct Layout {
+    int64_t tokens, masked, commit_step, resolved_bits, active0, active1, counters, anomalies,
+        partials, last_token, last_conf, last_p1, last_p2, last_tau, row_block, row_n_active,
+        row_n_commit, commit_log, total;
+    int64_t n_partials;
+    int32_t words_per_row;
+};
+
+int validate(const jot_params* p)
+{
+    if (!p) return JOT_ERR_NULL_POINTER;
+    if (p->dtype != JOT_F32 && p->dtype != JOT_BF16) return JOT_ERR_UNSUPPORTED_DTYPE;
+    if (p->B < 1 || p->L < 1 || p->V < 2) return JOT_ERR_INVALID_ARG;
+    if ((int64_t)p->B * p->L >= (int64_t)1 << 30) return JOT_ERR_INVALID_ARG;
+    if (p->conf_mode < JOT_CONF_RATIO || p->conf_mode > JOT_CONF_PROBGAP) return JOT_ERR_INVALID_ARG;
+    if (!(p->tau_min <= p->tau_max) || !isfinite(p->tau_min) || !isfinite(p->tau_max))
+        return JOT_ERR_INVALID_ARG;
+    if (!(p->gamma > 0.0f && p->gamma <= 1.0f)) return JOT_ERR_INVALID_ARG;
+    if (p->D < 0 || p->D > JOT_MAX_D) return JOT_ERR_INVALID_ARG;
+    if (!(p->eps >= 0.0f) || !isfinite(p->eps)) return JOT_ERR_INVALID_ARG;
+    if (p->gen_start < 0 || p->gen_start > p->L) return JOT_ERR_INVALID_ARG;
+    if (p->block_size < 0) return JOT_ERR_INVALID_ARG;
+    return JOT_OK;
+}
+
+int max_target_items() { return 4096 * kWgPerCu * kItemsPerWg; }   // bound used for sizing only
+
+Layout make_layout(const jot_params* p, int target_items)
+{
+    Layout l;
+    const int64_t n = (int64_t)p->B * p->L;
+    l.words_per_row = (p->L + 63) / 64;
+    l.n_partials = n + target_items;     // n_active * pieces <= n_active + target_items
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) { int64_t o = off; off = round_up(off + bytes, kAlign); return o; };
+    l.tokens = take(n * 4);
+    l.masked = take(n);
+    l.commit_step = take(n * 4);
+    l.resolved_bits = take((int64_t)p->B * l.words_per_row * 8);
+    l.active0 = take(n * 4);
+    l.active1 = take(n * 4);
+    l.counters = take(2 * sizeof(JotCounters));
+    l.anomalies = take(8);
+    l.partials = take(l.n_partials * (int64_t)sizeof(JotPartial));
+    l.last_token = take(n * 4);
+    l.last_conf = take(n * 4);
+    l.last_p1 = take(n * 4);
+    l.last_p2 = take(n * 4);
+    l.last_tau = take(n * 4);
+    l.row_block = take((int64_t)p->B * 4);
+    l.row_n_active = take((int64_t)p->B * 4);
+    l.row_n_commit = take((int64_t)p->B * 4);
+    l.commit_log = take(n * 12);
+    l.total = off;
+    return l;
+}
+
+struct HostCounters {
+    JotCounters c;
+    unsigned long long anomalies;
+};
+
+}  // namespace
+
+struct jot_state {
+    jot_params p;
+    Layout lay;
+    char* ws;
+    int cur;                    // which counter block / active list the next step reads
+    int32_t step;
+    int grid_reduce;
+    int target_items;
+    JotDecideParams decide;
+    JotCompactParams compact;
+    HostCounters* host;         // pinned
+    hipEvent_t done;
+    bool have_done;
+    bool profile;
+    hipEvent_t prof0, prof1;
+    bool prof_valid;
+
+    template <class T> T* at(int64_t off) const { return reinterpret_cast<T*>(ws + off); }
+    int32_t* active(int which) const { return at<int32_t>(which ? lay.active1 : lay.active0); }
+    JotCounters* counters(int which) const { return at<JotCounters>(lay.counters) + which; }
+};
+
+namespace {
+
+int enqueue_compaction(jot_state* s, int32_t step, hipStream_t st)
+{
+    const int in = s->cur, out = s->cur ^ 1;
+    hipLaunchKernelGGL(jot_row_count_kernel, dim3(s->p.B), dim3(JOT_WG), 0, st, s->compact, step,
+                       s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
+                       s->at<int32_t>(s->lay.row_block), s->at<int32_t>(s->lay.row_n_active),
+                       s->at<int32_t>(s->lay.row_n_commit));
+    hipLaunchKernelGGL(jot_row_write_kernel, dim3(s->p.B), dim3(JOT_WG), 0, st, s->compact, step,
+                       s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
+                       s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.row_block),
+                       s->at<int32_t>(s->lay.row_n_active), s->at<int32_t>(s->lay.row_n_commit),
+                       s->counters(in), s->counters(out), s->active(out),
+                       s->at<int32_t>(s->lay.commit_log), s->at<uint64_t>(s->lay.resolved_bits));
+    if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
+    // counters of the new state -> pinned host memory, then the event the host waits on
+    if (hipMemcpyAsync(&s->host->c, s->counters(out), sizeof(JotCounters), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return JOT_ERR_HIP;
+    if (hipMemcpyAsync(&s->host->anomalies, s->at<unsigned long long>(s->lay.anomalies), 8,
+                       hipMemcpyDeviceToHost, st) != hipSuccess)
+        return JOT_ERR_HIP;
+    if (hipEventRecord(s->done, st) != hipSuccess) return JOT_ERR_HIP;
+    s->have_done = true;
+    s->cur = out;
+    return JOT_OK;
+}
+
+int wait_done(jot_state* s)
+{
+    if (!s) return JOT_ERR_NULL_POINTER;
+    if (s->have_done && hipEventSynchronize(s->done) != hipSuccess) return JOT_ERR_HIP;
+    return JOT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t jot_workspace_bytes(const jot_params* p)
+{
+    const int rc = validate(p);
+    if (rc != JOT_OK) return rc;
+    return make_layout(p, max_target_items()).total;
+}
+
+int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, int64_t workspace_bytes,
+                   const int32_t* tokens_dev, const uint8_t* masked_dev, void* stream)
+{
+    if (!out) return JOT_ERR_NULL_POINTER;
+    *out = nullptr;
+    const int rc = validate(p);
+    if (rc != JOT_OK) return rc;
+    if (!workspace_dev || !tokens_dev || !masked_dev) return JOT_ERR_NULL_POINTER;
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign) return JOT_ERR_MISALIGNED;
+    if (reinterpret_cast<uintptr_t>(tokens_dev) % 4) return JOT_ERR_MISALIGNED;
+    if (workspace_bytes < make_layout(p, max_target_items()).total) return JOT_ERR_WORKSPACE_TOO_SMALL;
+
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return JOT_ERR_NO_DEVICE;
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        cus = kFallbackCus;
+    if (cus > 4096) cus = 4096;
+
+    jot_state* s = new (std::nothrow) jot_state();
+    if (!s) return JOT_ERR_INVALID_ARG;
+    s->p = *p;
+    s->ws = static_cast<char*>(workspace_dev);
+    s->grid_reduce = cus * kWgPerCu;
+    if (const char* e = getenv("JOT_REDUCE_WG_PER_CU")) {        // tuning aid, 1..16
+        const int v = atoi(e);
+        if (v >= 1 && v <= 16) s->grid_reduce = cus * v;
+    }
+    s->target_items = s->grid_reduce * kItemsPerWg;
+    if (s->target_items > max_target_items()) s->target_items = max_target_items();
+    s->lay = make_layout(p, max_target_items());
+    s->cur = 0;
+    s->step = 0;
+    s->have_done = false;
+    s->profile = false;
+    s->prof_valid = false;
+    s->host = nullptr;
+
+    JotDecideParams& d = s->decide;
+    memset(&d, 0, sizeof d);
+    d.L = p->L; d.V = p->V; d.conf_mode = p->conf_mode; d.D = p->D;
+    d.tau_max = p->tau_max; d.tau_min = p->tau_min; d.eps = p->eps;
+    d.words_per_row = s->lay.words_per_row;
+    d.target_items = s->target_items;
+    float wmax = 0.0f;
+    for (int k = 0; k <= JOT_MAX_D; ++k) d.gpow[k] = 0.0f;
+    for (int k = 1; k <= p->D; ++k) {
+        d.gpow[k] = (float)pow((double)p->gamma, (double)k);
+        wmax += d.gpow[k] * 2.0f;
+    }
+    d.wmax = p->D > 0 ? wmax : 1.0f;
+    s->compact.B = p->B; s->compact.L = p->L;
+    s->compact.gen_start = p->gen_start; s->compact.block_size = p->block_size;
+    s->compact.words_per_row = s->lay.words_per_row;
+
+    if (hipHostMalloc(reinterpret_cast<void**>(&s->host), sizeof(HostCounters), hipHostMallocDefault) != hipSuccess) {
+        delete s;
+        return JOT_ERR_HIP;
+    }
+    memset(s->host, 0, sizeof(HostCounters));
+    if (hipEventCreateWithFlags(&s->done, hipEventDisableTiming) != hipSuccess) {
+        (void)hipHostFree(s->host);
+        delete s;
+        return JOT_ERR_HIP;
+    }
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t n = (int64_t)p->B * p->L;
+    hipLaunchKernelGGL(jot_init_copy_kernel, dim3((unsigned)((n + JOT_WG - 1) / JOT_WG)), dim3(JOT_WG), 0, st,
+                       n, tokens_dev, masked_dev, s->at<int32_t>(s->lay.tokens),
+                       s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
+                       s->counters(0), s->at<unsigned long long>(s->lay.anomalies));
+    int rc2 = (hipGetLastError() == hipSuccess) ? enqueue_compaction(s, /*step=*/-1, st) : JOT_ERR_HIP;
+    if (rc2 == JOT_OK && hipStreamSynchronize(st) != hipSuccess) rc2 = JOT_ERR_HIP;
+    if (rc2 != JOT_OK) {
+        jot_release(s);
+        return rc2;
+    }
+    *out = s;
+    return JOT_OK;
+}
+
+int jot_step(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l, void* stream)
+{
+    if (!s || !logits_dev) return JOT_ERR_NULL_POINTER;
+    const jot_params& p = s->p;
+    const int64_t esz = p.dtype == JOT_F32 ? 4 : 2;
+    if (stride_l < p.V) return JOT_ERR_INVALID_ARG;
+    if (p.B > 1 && stride_b < (int64_t)(p.L - 1) * stride_l + p.V) return JOT_ERR_INVALID_ARG;
+    if (stride_b < 0) return JOT_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(logits_dev) % 16 || (stride_l * esz) % 16 ||
+        (p.B > 1 && (stride_b * esz) % 16))
+        return JOT_ERR_MISALIGNED;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int32_t step = s->step + 1;
+    const int in = s->cur;
+    const int64_t n = (int64_t)p.B * p.L;
+
+    if (s->profile && hipEventRecord(s->prof0, st) != hipSuccess) return JOT_ERR_HIP;
+    if (p.dtype == JOT_F32)
+        hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotF32>, dim3(s->grid_reduce), dim3(JOT_WG), 0, st,
+                           logits_dev, stride_b, stride_l, p.L, p.V, s->active(in), s->counters(in),
+                           s->at<JotPartial>(s->lay.partials), s->target_items);
+    else
+        hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotBF16>, dim3(s->grid_reduce), dim3(JOT_WG), 0, st,
+                           logits_dev, stride_b, stride_l, p.L, p.V, s->active(in), s->counters(in),
+                           s->at<JotPartial>(s->lay.partials), s->target_items);
+    if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
+    if (s->profile) {
+        if (hipEventRecord(s->prof1, st) != hipSuccess) return JOT_ERR_HIP;
+        s->prof_valid = true;
+    }
+
+    hipLaunchKernelGGL(jot_decide_kernel, dim3((unsigned)((n + JOT_WG - 1) / JOT_WG)), dim3(JOT_WG), 0, st,
+                       s->decide, step, s->active(in), s->counters(in), s->at<JotPartial>(s->lay.partials),
+                       s->at<uint64_t>(s->lay.resolved_bits), s->at<int32_t>(s->lay.tokens),
+                       s->at<int32_t>(s->lay.commit_step), s->at<int32_t>(s->lay.last_token),
+                       s->at<float>(s->lay.last_conf), s->at<float>(s->lay.last_p1),
+                       s->at<float>(s->lay.last_p2), s->at<float>(s->lay.last_tau),
+                       s->at<unsigned long long>(s->lay.anomalies));
+    if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
+    s->step = step;
+    return enqueue_compaction(s, step, st);
+}
+
+int64_t jot_active_count(jot_state* s)
+{
+    const int rc = wait_done(s);
+    return rc != JOT_OK ? rc : s->host->c.n_active;
+}
+
+int32_t jot_step_index(const jot_state* s) { return s ? s->step : JOT_ERR_NULL_POINTER; }
+
+int64_t jot_anomaly_count(jot_state* s)
+{
+    const int rc = wait_done(s);
+    return rc != JOT_OK ? rc : (int64_t)s->host->anomalies;
+}
+
+const int32_t* jot_tokens(const jot_state* s) { return s ? s->at<int32_t>(s->lay.tokens) : nullptr; }
+const uint8_t* jot_masked(const jot_state* s) { return s ? s->at<uint8_t>(s->lay.masked) : nullptr; }
+const int32_t* jot_commit_step(const jot_state* s) { return s ? s->at<int32_t>(s->lay.commit_step) : nullptr; }
+const int32_t* jot_active_list(const jot_state* s) { return s ? s->active(s->cur) : nullptr; }
+
+const int32_t* jot_commit_log(jot_state* s, int64_t* n)
+{
+    if (!s || !n || wait_done(s) != JOT_OK) return nullptr;
+    *n = s->host->c.n_log;
+    return s->at<int32_t>(s->lay.commit_log);
+}
+
+const int32_t* jot_examined_list(jot_state* s, int64_t* n)
+{
+    if (!s || !n || wait_done(s) != JOT_OK) return nullptr;
+    *n = s->host->c.n_examined;
+    return s->active(s->cur ^ 1);
+}
+
+const int32_t* jot_last_token(const jot_state* s) { return s ? s->at<int32_t>(s->lay.last_token) : nullptr; }
+const float* jot_last_conf(const jot_state* s) { return s ? s->at<float>(s->lay.last_conf) : nullptr; }
+const float* jot_last_p1(const jot_state* s) { return s ? s->at<float>(s->lay.last_p1) : nullptr; }
+const float* jot_last_p2(const jot_state* s) { return s ? s->at<float>(s->lay.last_p2) : nullptr; }
+const float* jot_last_tau(const jot_state* s) { return s ? s->at<float>(s->lay.last_tau) : nullptr; }
+
+int jot_profile_enable(jot_state* s, int on)
+{
+    if (!s) return JOT_ERR_NULL_POINTER;
+    if (on && !s->profile) {
+        if (hipEventCreate(&s->prof0) != hipSuccess) return JOT_ERR_HIP;
+        if (hipEventCreate(&s->prof1) != hipSuccess) { (void)hipEventDestroy(s->prof0); return JOT_ERR_HIP; }
+        s->profile = true;
+        s->prof_valid = false;
+    } else if (!on && s->profile) {
+        (void)hipEventDestroy(s->prof0);
+        (void)hipEventDestroy(s->prof1);
+        s->profile = false;
+        s->prof_valid = false;
+    }
+    return JOT_OK;
+}
+
+int jot_profile_read(jot_state* s, float* vocab_reduce_ms)
+{
+    if (!s || !vocab_reduce_ms) return JOT_ERR_NULL_POINTER;
+    if (!s->profile || !s->prof_valid) return JOT_ERR_INVALID_ARG;
+    if (hipEventSynchronize(s->prof1) != hipSuccess) return JOT_ERR_HIP;
+    if (hipEventElapsedTime(vocab_reduce_ms, s->prof0, s->prof1) != hipSuccess) return JOT_ERR_HIP;
+    return JOT_OK;
+}
+
+void jot_release(jot_state* s)
+{
+    if (!s) return;
+    if (s->profile) {
+        (void)hipEventDestroy(s->prof0);
+        (void)hipEventDestroy(s->prof1);
+    }
+    (void)hipEventDestroy(s->done);
+    if (s->host) (void)hipHostFree(s->host);
+    delete s;
+}
+
+const char* jot_strerror(int code)
+{
+    switch (code) {
+    case JOT_OK: return "success";
+    case JOT_ERR_INVALID_ARG: return "invalid argument";
+    case JOT_ERR_NULL_POINTER: return "null pointer";
+    case JOT_ERR_UNSUPPORTED_DTYPE: return "unsupported logit dtype";
+    case JOT_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case JOT_ERR_MISALIGNED: return "misaligned pointer or stride";
+    case JOT_ERR_HIP: return "HIP runtime error";
+    case JOT_ERR_NO_DEVICE: return "no HIP device";
+    default: return "unknown error";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,184 @@
+// Mask maintenance and ordered stream compaction (Algorithm 1: M_{n+1} = positions still [M]).
+//
+// After the decisions of step n, two small kernels -- one workgroup per batch row -- turn
+// "commit_step == n" into: the updated byte mask, the bit image of resolved positions that the
+// next step's Eq. 3 reads, the next list of examined positions (ascending b*L+i) and the
+// commit-log entries of this step (ascending b*L+i).  Order is fixed by construction (wave
+// ballots and prefix counts), never by the arrival order of atomics.
+//
+// Block mode (semi-autoregressive decoding): a row's examined positions are the masked
+// positions of the block that holds its lowest masked position; blocks have block_size
+// positions and are counted from gen_start.
+#pragma once
+#include "jot_device.h"
+
+struct JotCompactParams {
+    int32_t B, L;
+    int32_t gen_start, block_size;
+    int32_t words_per_row;
+};
+
+__device__ __forceinline__ int jot_floor_div(int a, int b)   // b > 0
+{
+    int q = a / b;
+    return (a % b < 0) ? q - 1 : q;
+}
+
+__device__ __forceinline__ int jot_block_reduce_min(int v, int* lds)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+        v = min(v, __shfl_xor(v, off, 64));
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    int r = lds[0];
+#pragma unroll
+    for (int k = 1; k < JOT_WAVES; ++k) r = min(r, lds[k]);
+    __syncthreads();
+    return r;
+}
+
+__device__ __forceinline__ int jot_block_reduce_sum(int v, int* lds)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+        v += __shfl_xor(v, off, 64);
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    int r = 0;
+#pragma unroll
+    for (int k = 0; k < JOT_WAVES; ++k) r += lds[k];
+    __syncthreads();
+    return r;
+}
+
+// Pass 1: per batch row, the block currently being decoded and the two counts.
+__global__ __launch_bounds__(JOT_WG) void jot_row_count_kernel(
+    JotCompactParams prm, int32_t step, const uint8_t* __restrict__ masked,
+    const int32_t* __restrict__ commit_step, int32_t* __restrict__ row_block,
+    int32_t* __restrict__ row_n_active, int32_t* __restrict__ row_n_commit)
+{
+    __shared__ int lds[JOT_WAVES];
+    const int b = blockIdx.x;
+    const int64_t base = (int64_t)b * prm.L;
+    int first = 0x7fffffff;
+    for (int i = threadIdx.x; i < prm.L; i += JOT_WG) {
+        const bool still = masked[base + i] && commit_step[base + i] != step;
+        if (still) first = min(first, i);
+    }
+    first = jot_block_reduce_min(first, lds);
+    int blk = 0;
+    if (prm.block_size > 0 && first != 0x7fffffff)
+        blk = jot_floor_div(first - prm.gen_start, prm.block_size);
+    int n_act = 0, n_com = 0;
+    for (int i = threadIdx.x; i < prm.L; i += JOT_WG) {
+        const bool was = masked[base + i] != 0;
+        const bool com = was && commit_step[base + i] == step;
+        const bool still = was && !com;
+        const bool elig = still &&
+            (prm.block_size <= 0 || jot_floor_div(i - prm.gen_start, prm.block_size) == blk);
+        n_act += elig ? 1 : 0;
+        n_com += com ? 1 : 0;
+    }
+    n_act = jot_block_reduce_sum(n_act, lds);
+    n_com = jot_block_reduce_sum(n_com, lds);
+    if (threadIdx.x == 0) {
+        row_block[b] = blk;
+        row_n_active[b] = n_act;
+        row_n_commit[b] = n_com;
+    }
+}
+
+// Pass 2: exclusive prefix over rows, then ordered writes.
+__global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
+    JotCompactParams prm, int32_t step, uint8_t* __restrict__ masked,
+    const int32_t* __restrict__ commit_step, const int32_t* __restrict__ tokens,
+    const int32_t* __restrict__ row_block, const int32_t* __restrict__ row_n_active,
+    const int32_t* __restrict__ row_n_commit, const JotCounters* __restrict__ cnt_in,
+    JotCounters* __restrict__ cnt_out, int32_t* __restrict__ active_out,
+    int32_t* __restrict__ commit_log, uint64_t* __restrict__ resolved_bits)
+{
+    __shared__ int lds[JOT_WAVES];
+    __shared__ int wave_act[JOT_WAVES], wave_com[JOT_WAVES];
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t base = (int64_t)b * prm.L;
+
+    int pa = 0, pc = 0;
+    for (int k = threadIdx.x; k < b; k += JOT_WG) {
+        pa += row_n_active[k];
+        pc += row_n_commit[k];
+    }
+    const int64_t act_base = jot_block_reduce_sum(pa, lds);
+    const int64_t com_prefix = jot_block_reduce_sum(pc, lds);
+    const int64_t log_base = cnt_in->n_log + com_prefix;
+    const int blk = row_block[b];
+
+    int run_act = 0, run_com = 0;
+    for (int c0 = 0; c0 < prm.L; c0 += JOT_WG) {
+        const int i = c0 + threadIdx.x;
+        const bool in = i < prm.L;
+        const bool was = in && masked[base + i] != 0;
+        const bool com = was && commit_step[base + i] == step;
+        const bool still = was && !com;
+        const bool elig = still &&
+            (prm.block_size <= 0 || jot_floor_div(i - prm.gen_start, prm.block_size) == blk);
+        const uint64_t m_act = __ballot(elig);
+        const uint64_t m_com = __ballot(com);
+        const uint64_t m_res = __ballot(in && !still);
+        const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+        if (lane == 0) {
+            wave_act[wave] = __popcll(m_act);
+            wave_com[wave] = __popcll(m_com);
+            if (c0 + wave * 64 < prm.words_per_row * 64)
+                resolved_bits[(int64_t)b * prm.words_per_row + ((c0 + wave * 64) >> 6)] = m_res;
+        }
+        __syncthreads();
+        int off_act = run_act, off_com = run_com, tot_act = 0, tot_com = 0;
+#pragma unroll
+        for (int k = 0; k < JOT_WAVES; ++k) {
+            if (k < wave) { off_act += wave_act[k]; off_com += wave_com[k]; }
+            tot_act += wave_act[k];
+            tot_com += wave_com[k];
+        }
+        if (elig)
+            active_out[act_base + off_act + __popcll(m_act & below)] = (int32_t)(base + i);
+        if (com) {
+            int32_t* e = commit_log + 3 * (log_base + off_com + __popcll(m_com & below));
+            e[0] = step;
+            e[1] = (int32_t)(base + i);
+            e[2] = tokens[base + i];
+            masked[base + i] = 0;
+        }
+        run_act += tot_act;
+        run_com += tot_com;
+        __syncthreads();
+    }
+    if (b == prm.B - 1 && threadIdx.x == 0) {
+        cnt_out->n_active = act_base + run_act;
+        cnt_out->n_log = log_base + run_com;
+        cnt_out->n_examined = cnt_in->n_active;
+        cnt_out->reserved = 0;
+    }
+}
+
+// Copy of the caller's initial canvas into the workspace.
+__global__ __launch_bounds__(JOT_WG) void jot_init_copy_kernel(
+    int64_t n, const int32_t* __restrict__ tokens_in, const uint8_t* __restrict__ masked_in,
+    int32_t* __restrict__ tokens, uint8_t* __restrict__ masked, int32_t* __restrict__ commit_step,
+    JotCounters* __restrict__ cnt0, unsigned long long* __restrict__ anomalies)
+{
+    const int64_t k = (int64_t)blockIdx.x * JOT_WG + threadIdx.x;
+    if (k < n) {
+        tokens[k] = tokens_in[k];
+        masked[k] = masked_in[k] ? 1 : 0;
+        commit_step[k] = 0;
+    }
+    if (k == 0) {
+        cnt0->n_active = 0;
+        cnt0->n_log = 0;
+        cnt0->n_examined = 0;
+        cnt0->reserved = 0;
+        *anomalies = 0ull;
+    }
+}

@@ -1,0 +1,93 @@
+// Confidence, spatially adaptive threshold and the finalization decision (Eq. 2 - Eq. 6).
+//
+// One thread per examined position.  It merges the pieces of its row, forms (p1, p2) and the
+// selected confidence signal, evaluates Eq. 3 from a bit image of the step-start mask (bit = 1
+// where a position is resolved; bits outside the canvas are 0), and tests Eq. 6.  A finalized
+// position gets its token and the step number; the mask itself is updated by the compaction
+// kernels afterwards, so every thread of this kernel sees the mask as it was when the step began.
+#pragma once
+#include "jot_device.h"
+
+struct JotDecideParams {
+    int32_t L, V;
+    int32_t conf_mode;
+    int32_t D;
+    float tau_max, tau_min, eps;
+    float wmax;                   // 2 * sum_{d=1..D} gamma^d, summed in float in the order d = 1..D
+    int32_t words_per_row;        // 64-bit words of the resolved-bit image per batch row
+    int32_t target_items;
+    float gpow[JOT_MAX_D + 1];    // gpow[d] = gamma^d
+};
+
+__global__ __launch_bounds__(JOT_WG) void jot_decide_kernel(
+    JotDecideParams prm, int32_t step,
+    const int32_t* __restrict__ active, const JotCounters* __restrict__ counters,
+    const JotPartial* __restrict__ partials, const uint64_t* __restrict__ resolved_bits,
+    int32_t* __restrict__ tokens, int32_t* __restrict__ commit_step,
+    int32_t* __restrict__ last_token, float* __restrict__ last_conf, float* __restrict__ last_p1,
+    float* __restrict__ last_p2, float* __restrict__ last_tau,
+    unsigned long long* __restrict__ anomalies)
+{
+    const int64_t n_active = counters->n_active;
+    const int64_t r = (int64_t)blockIdx.x * JOT_WG + threadIdx.x;
+    if (r >= n_active)
+        return;
+    const JotSplit sp = jot_plan_split(n_active, prm.V, prm.target_items);
+
+    // ---- merge the pieces of the row, in piece order
+    const JotPartial* q = partials + r * sp.S;
+    float m1 = q[0].m1, m2 = q[0].m2, M = q[0].M, s = q[0].s;
+    int32_t idx = q[0].idx;
+    for (int j = 1; j < sp.S; ++j)
+        jot_merge(m1, idx, m2, M, s, q[j].m1, q[j].idx, q[j].m2, q[j].M, q[j].s);
+
+    // ---- probabilities: S = sum_v exp(l_v - m1) = s * 2^(M - m1*log2 e); p1 = 1/S, p2 = e^(m2-m1)/S
+    const float S = s * exp2f(fmaf(-m1, JOT_LOG2E, M));
+    const bool has_softmax = (S >= 0.5f) && (S < INFINITY) && (m1 < INFINITY);   // false for NaN
+    const float p1 = 1.0f / S;
+    const float p2 = expf(m2 - m1) / S;
+    float conf;
+    if (prm.conf_mode == 0)
+        conf = p1 / (p2 + prm.eps);          // Eq. 2
+    else if (prm.conf_mode == 1)
+        conf = p1;
+    else
+        conf = p1 - p2;
+
+    // ---- Eq. 3: neighbours at distance d = 1..D on both sides, from the bit image
+    const int pos = active[r];
+    const int b = pos / prm.L;
+    const int i = pos - b * prm.L;
+    float phi = 0.0f;
+    if (prm.D > 0) {
+        const uint64_t* words = resolved_bits + (int64_t)b * prm.words_per_row;
+        const int wi = i >> 6, bi = i & 63;
+        const uint64_t mid = words[wi];
+        const uint64_t lo = wi > 0 ? words[wi - 1] : 0ull;
+        const uint64_t hi = (wi + 1 < prm.words_per_row) ? words[wi + 1] : 0ull;
+        // left: bit 63 = position i, bit 63-d = position i-d
+        const uint64_t left = (mid << (63 - bi)) | (bi == 63 ? 0ull : (lo >> (bi + 1)));
+        // right: bit 0 = position i, bit d = position i+d
+        const uint64_t right = (mid >> bi) | (bi == 0 ? 0ull : (hi << (64 - bi)));
+        float w = 0.0f;
+        for (int d = 1; d <= prm.D; ++d) {
+            const int cnt = (int)((left >> (63 - d)) & 1ull) + (int)((right >> d) & 1ull);
+            w += prm.gpow[d] * (float)cnt;
+        }
+        phi = fminf(1.0f, w / prm.wmax);                        // Eq. 4 (w == wmax exactly when all 2D are resolved)
+    }
+    const float tau = prm.tau_max - (prm.tau_max - prm.tau_min) * phi;   // Eq. 5
+
+    const bool commit = has_softmax && (conf >= tau);           // Eq. 6
+    if (commit) {
+        tokens[pos] = idx;
+        commit_step[pos] = step;
+    }
+    if (!has_softmax)
+        atomicAdd(anomalies, 1ull);
+    last_token[r] = idx;
+    last_conf[r] = has_softmax ? conf : __uint_as_float(0x7fc00000u);
+    last_p1[r] = p1;
+    last_p2[r] = p2;
+    last_tau[r] = tau;
+}

@@ -1,0 +1,77 @@
+// Shared device-side definitions of the finalization pass (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define JOT_WG 256                 // threads per workgroup of every kernel here (4 waves)
+#define JOT_WAVES (JOT_WG / 64)
+#define JOT_CHUNK_ALIGN 2048       // vocabulary split points are multiples of this many elements
+#define JOT_MIN_CHUNK 8192         // never split a row into pieces smaller than this
+#define JOT_MAX_D 32
+
+// Partial result of the vocabulary reduction over a contiguous piece of one logit row.
+// The exponentials are accumulated in base 2 against an integer-valued reference M:
+//   s = sum_v 2^(l_v * log2(e) - M),  so that  sum_v exp(l_v - m1) = s * 2^(M - m1 * log2(e)).
+struct __align__(32) JotPartial {
+    float m1;       // largest logit of the piece (-inf if the piece is empty)
+    int32_t idx;    // its vocabulary index, smallest index among equal maxima
+    float m2;       // second largest logit of the piece as a multiset
+    float M;        // reference exponent (integer valued, -inf if nothing finite was seen)
+    float s;        // scaled sum of exponentials
+    float pad[3];
+};
+
+struct JotSplit {
+    int S;          // pieces per row
+    int chunk;      // elements per piece (multiple of JOT_CHUNK_ALIGN unless S == 1)
+};
+
+// How a step with n_active examined rows cuts each row so that the persistent grid has about
+// target_items work items.  Evaluated identically by every kernel of the step.
+__host__ __device__ inline JotSplit jot_plan_split(int64_t n_active, int V, int target_items)
+{
+    JotSplit sp;
+    sp.S = 1;
+    sp.chunk = V;
+    if (n_active <= 0 || n_active >= target_items)
+        return sp;
+    int64_t want = (target_items + n_active - 1) / n_active;
+    int max_s = V / JOT_MIN_CHUNK;
+    if (max_s < 1) max_s = 1;
+    int s0 = want < max_s ? (int)want : max_s;
+    if (s0 <= 1)
+        return sp;
+    int chunk = (V + s0 - 1) / s0;
+    chunk = (chunk + JOT_CHUNK_ALIGN - 1) / JOT_CHUNK_ALIGN * JOT_CHUNK_ALIGN;
+    sp.chunk = chunk;
+    sp.S = (V + chunk - 1) / chunk;
+    return sp;
+}
+
+// Device counters, double buffered: step k reads block [cur] and writes block [cur ^ 1].
+struct JotCounters {
+    int64_t n_active;     // positions the next step examines
+    int64_t n_log;        // commit-log triples written so far
+    int64_t n_examined;   // positions the last step examined
+    int64_t reserved;
+};
+
+#define JOT_LOG2E 1.44269504088896340736f
+
+// Lexicographic merge of two pieces of the same row: larger logit first, then smaller index.
+// m2 is the second entry of the merged multiset; the sums are brought to the common reference.
+__device__ __forceinline__ void jot_merge(float& m1, int32_t& idx, float& m2, float& M, float& s,
+                                          float bm1, int32_t bidx, float bm2, float bM, float bs)
+{
+    const bool a_wins = (m1 > bm1) || (m1 == bm1 && idx < bidx);
+    const float loser = a_wins ? bm1 : m1;
+    m2 = fmaxf(fmaxf(m2, bm2), loser);
+    idx = a_wins ? idx : bidx;
+    m1 = a_wins ? m1 : bm1;
+    const float newM = fmaxf(M, bM);
+    // references are integer valued, so these scalings are exact powers of two
+    const float fa = (M == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(M - newM);
+    const float fb = (bM == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(bM - newM);
+    s = s * fa + bs * fb;
+    M = newM;
+}

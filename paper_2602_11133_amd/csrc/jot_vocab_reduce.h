@@ -1,0 +1,209 @@
+// Vocabulary reduction: the one kernel that reads the logits.
+//
+// For each examined position it produces what Section 4.1 ("Confidence Metric") needs from the
+// row l in R^V: the argmax (smallest index among equal maxima), the two largest logits m1 >= m2
+// of the multiset, and sum_v exp(l_v - m1) -- hence p1 = 1/S and p2 = exp(m2 - m1)/S -- in ONE
+// pass over the row, so the row is fetched from HBM exactly once.
+//
+// Launch shape: a persistent grid.  Work items are (examined row, piece of the row); workgroup w
+// handles items w, w + G, w + 2G, ...  The number of examined rows lives in device memory (it is
+// produced by the previous step), so the loop bound is read on the device and the launch itself
+// never depends on it.  Each of the 256 threads streams 16-byte vectors, 256 vectors apart, and
+// keeps its running state in registers; a wave-level butterfly and a 4-entry LDS exchange
+// combine the 256 lane states into one JotPartial.
+#pragma once
+#include "jot_device.h"
+
+typedef uint32_t jot_u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte load
+
+struct JotLane {
+    float m1, m2;
+    int32_t idx;
+    float M;            // integer-valued reference of the base-2 exponentials, -inf until set
+    float s0, s1, s2, s3;
+};
+
+__device__ __forceinline__ void jot_lane_init(JotLane& a)
+{
+    a.m1 = -INFINITY;
+    a.m2 = -INFINITY;
+    a.idx = 0x7fffffff;
+    a.M = -INFINITY;
+    a.s0 = a.s1 = a.s2 = a.s3 = 0.0f;
+}
+
+// top-2 and argmax of the lane, N consecutive elements starting at vocabulary index vbase
+template <int N>
+__device__ __forceinline__ void jot_top2(JotLane& a, const float (&x)[N], int vbase)
+{
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const float xv = x[k];
+        a.m2 = __builtin_amdgcn_fmed3f(a.m1, a.m2, xv);   // second of {m1, m2, x}
+        a.idx = (xv > a.m1) ? (vbase + k) : a.idx;        // strict: first maximum keeps the index
+        a.m1 = fmaxf(a.m1, xv);
+    }
+}
+
+// Keep every exponent l*log2(e) - M of the lane at or below 32: when the running maximum has
+// climbed past that, move the reference to it and rescale the sums (exact: M is an integer).
+__device__ __forceinline__ void jot_rereference(JotLane& a)
+{
+    const float t = a.m1 * JOT_LOG2E;
+    if (t > a.M + 32.0f) {
+        const float newM = ceilf(t);
+        const float f = (a.M == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(a.M - newM);
+        a.s0 *= f; a.s1 *= f; a.s2 *= f; a.s3 *= f;
+        a.M = newM;
+    }
+}
+
+template <int N>
+__device__ __forceinline__ void jot_expsum(JotLane& a, const float (&x)[N])
+{
+    const float negM = (a.M == -INFINITY) ? 0.0f : -a.M;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const float e = __builtin_amdgcn_exp2f(fmaf(x[k], JOT_LOG2E, negM));
+        if ((k & 3) == 0) a.s0 += e;
+        else if ((k & 3) == 1) a.s1 += e;
+        else if ((k & 3) == 2) a.s2 += e;
+        else a.s3 += e;
+    }
+}
+
+// ---- element types -------------------------------------------------------------------------
+struct JotF32 {
+    static constexpr int VEC = 4;              // elements per 16-byte vector
+    static constexpr int ESZ = 4;
+    static constexpr int UNROLL = 8;           // vectors in flight per thread
+    __device__ static __forceinline__ void unpack(const jot_u32x4& w, float (&x)[VEC])
+    {
+        x[0] = __uint_as_float(w.x); x[1] = __uint_as_float(w.y);
+        x[2] = __uint_as_float(w.z); x[3] = __uint_as_float(w.w);
+    }
+    __device__ static __forceinline__ float scalar(const void* row, int v)
+    {
+        return reinterpret_cast<const float*>(row)[v];
+    }
+};
+
+struct JotBF16 {
+    static constexpr int VEC = 8;
+    static constexpr int ESZ = 2;
+    static constexpr int UNROLL = 4;
+    // a bf16 is the upper half of a binary32: widening is a shift / mask, exact
+    __device__ static __forceinline__ void unpack(const jot_u32x4& w, float (&x)[VEC])
+    {
+        x[0] = __uint_as_float(w.x << 16); x[1] = __uint_as_float(w.x & 0xffff0000u);
+        x[2] = __uint_as_float(w.y << 16); x[3] = __uint_as_float(w.y & 0xffff0000u);
+        x[4] = __uint_as_float(w.z << 16); x[5] = __uint_as_float(w.z & 0xffff0000u);
+        x[6] = __uint_as_float(w.w << 16); x[7] = __uint_as_float(w.w & 0xffff0000u);
+    }
+    __device__ static __forceinline__ float scalar(const void* row, int v)
+    {
+        return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(row)[v] << 16);
+    }
+};
+
+template <class T>
+__global__ __launch_bounds__(JOT_WG) void jot_vocab_reduce_kernel(
+    const void* __restrict__ logits, int64_t stride_b, int64_t stride_l, int L, int V,
+    const int32_t* __restrict__ active, const JotCounters* __restrict__ counters,
+    JotPartial* __restrict__ partials, int target_items)
+{
+    constexpr int VEC = T::VEC;
+    constexpr int U = T::UNROLL;
+    const int64_t n_active = counters->n_active;
+    const JotSplit sp = jot_plan_split(n_active, V, target_items);
+    const int64_t n_items = n_active * sp.S;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    __shared__ JotPartial wave_part[JOT_WAVES];
+
+    for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int64_t r = item / sp.S;
+        const int piece = (int)(item - r * sp.S);
+        const int pos = active[r];
+        const int b = pos / L;
+        const int i = pos - b * L;
+        const char* row = reinterpret_cast<const char*>(logits) +
+                          ((int64_t)b * stride_b + (int64_t)i * stride_l) * T::ESZ;
+        const int v0 = piece * sp.chunk;                       // multiple of JOT_CHUNK_ALIGN
+        const int v1 = min(V, v0 + sp.chunk);
+        const int nvec = (v1 - v0) / VEC;                      // whole 16-byte vectors
+        const jot_u32x4* __restrict__ p =
+            reinterpret_cast<const jot_u32x4*>(row + (int64_t)v0 * T::ESZ);
+
+        JotLane a;
+        jot_lane_init(a);
+
+        int c = tid;
+        for (; c + (U - 1) * JOT_WG < nvec; c += U * JOT_WG) {
+            jot_u32x4 w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                w[u] = __builtin_nontemporal_load(p + c + u * JOT_WG);
+            float x[U][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                T::unpack(w[u], x[u]);
+                jot_top2<VEC>(a, x[u], v0 + (c + u * JOT_WG) * VEC);
+            }
+            jot_rereference(a);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                jot_expsum<VEC>(a, x[u]);
+        }
+        for (; c < nvec; c += JOT_WG) {
+            const jot_u32x4 w = __builtin_nontemporal_load(p + c);
+            float x[VEC];
+            T::unpack(w, x);
+            jot_top2<VEC>(a, x, v0 + c * VEC);
+            jot_rereference(a);
+            jot_expsum<VEC>(a, x);
+        }
+        {   // elements after the last whole vector (V not a multiple of VEC; last piece only)
+            const int v = v0 + nvec * VEC + tid;
+            if (v < v1) {
+                float x[1] = { T::scalar(row, v) };
+                jot_top2<1>(a, x, v);
+                jot_rereference(a);
+                jot_expsum<1>(a, x);
+            }
+        }
+
+        // lane -> wave
+        float s = (a.s0 + a.s1) + (a.s2 + a.s3);
+        float m1 = a.m1, m2 = a.m2, M = a.M;
+        int32_t idx = a.idx;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float bm1 = __shfl_xor(m1, off, 64);
+            const int32_t bidx = __shfl_xor(idx, off, 64);
+            const float bm2 = __shfl_xor(m2, off, 64);
+            const float bM = __shfl_xor(M, off, 64);
+            const float bs = __shfl_xor(s, off, 64);
+            jot_merge(m1, idx, m2, M, s, bm1, bidx, bm2, bM, bs);
+        }
+        // wave -> workgroup
+        if (lane == 0) {
+            JotPartial q;
+            q.m1 = m1; q.idx = idx; q.m2 = m2; q.M = M; q.s = s;
+            q.pad[0] = q.pad[1] = q.pad[2] = 0.0f;
+            wave_part[wave] = q;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            JotPartial q = wave_part[0];
+#pragma unroll
+            for (int k = 1; k < JOT_WAVES; ++k) {
+                const JotPartial o = wave_part[k];
+                jot_merge(q.m1, q.idx, q.m2, q.M, q.s, o.m1, o.idx, o.m2, o.M, o.s);
+            }
+            partials[item] = q;
+        }
+        __syncthreads();
+    }
+}

@@ -1,0 +1,119 @@
+"""GPU side of the parity tests: drives the C-ABI library through the Python binding and
+reads its results back.  torch supplies device memory and the stream, nothing else."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2602_11133_amd as J
+from gen.configs import F32
+
+
+def params_of(cfg) -> J.JotParams:
+    return J.JotParams(B=cfg.B, L=cfg.L, V=cfg.V, dtype=cfg.dtype, conf_mode=cfg.conf_mode,
+                       tau_max=cfg.tau_max, tau_min=cfg.tau_min, gamma=cfg.gamma, D=cfg.D,
+                       eps=cfg.eps, gen_start=cfg.gen_start, block_size=cfg.block_size)
+
+
+class GpuJot:
+    """One decoding state on the GPU."""
+
+    def __init__(self, params: J.JotParams, tokens: np.ndarray, masked: np.ndarray, device="cuda:0"):
+        self.p = params
+        self.dev = torch.device(device)
+        self.n = params.B * params.L
+        self.ws_bytes = J.jot_workspace_bytes(params)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
+        assert self.ws.data_ptr() % 256 == 0
+        tok = torch.from_numpy(np.ascontiguousarray(tokens, np.int32)).to(self.dev)
+        msk = torch.from_numpy(np.ascontiguousarray(masked, np.uint8)).to(self.dev)
+        self.stream = torch.cuda.current_stream().cuda_stream
+        self.h = J.jot_init_state(params, self.ws.data_ptr(), self.ws_bytes, tok.data_ptr(),
+                                  msk.data_ptr(), self.stream)
+
+    def close(self):
+        if self.h:
+            torch.cuda.synchronize()
+            J.jot_release(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def step(self, logits: torch.Tensor, stride_b=None, stride_l=None):
+        sb = logits.stride(0) if stride_b is None else stride_b
+        sl = logits.stride(1) if stride_l is None else stride_l
+        J.jot_step(self.h, logits.data_ptr(), sb, sl, self.stream)
+
+    # ---- read-back
+    def active_count(self) -> int:
+        return J.jot_active_count(self.h)
+
+    def active_list(self) -> np.ndarray:
+        n = self.active_count()
+        return J.device_to_host(J.jot_active_list(self.h), n, np.int32)
+
+    def tokens(self) -> np.ndarray:
+        self.active_count()
+        return J.device_to_host(J.jot_tokens(self.h), self.n, np.int32).reshape(self.p.B, self.p.L)
+
+    def masked(self) -> np.ndarray:
+        self.active_count()
+        return J.device_to_host(J.jot_masked(self.h), self.n, np.uint8).reshape(self.p.B, self.p.L).astype(bool)
+
+    def commit_step(self) -> np.ndarray:
+        self.active_count()
+        return J.device_to_host(J.jot_commit_step(self.h), self.n, np.int32).reshape(self.p.B, self.p.L)
+
+    def commit_log(self) -> np.ndarray:
+        ptr, n = J.jot_commit_log(self.h)
+        return J.device_to_host(ptr, 3 * n, np.int32).reshape(n, 3)
+
+    def last(self) -> dict:
+        ptr, n = J.jot_examined_list(self.h)
+        out = {"active": J.device_to_host(ptr, n, np.int32)}
+        out["token"] = J.device_to_host(J.jot_last_token(self.h), n, np.int32)
+        for name in ("conf", "p1", "p2", "tau"):
+            out[name] = J.device_to_host(getattr(J, "jot_last_" + name)(self.h), n, np.float32)
+        return out
+
+
+def upload_rows(logits: torch.Tensor, positions: np.ndarray, rows: np.ndarray, dtype: int) -> None:
+    """Write host rows ([n, V] float32 or bf16 bit patterns) into logits[b, i, :] for the given
+    flattened positions."""
+    B, L, V = logits.shape
+    flat = logits.view(B * L, V)
+    idx = torch.from_numpy(np.ascontiguousarray(positions, np.int64)).to(logits.device)
+    if dtype == F32:
+        src = torch.from_numpy(np.ascontiguousarray(rows, np.float32)).to(logits.device)
+    else:
+        src = torch.from_numpy(np.ascontiguousarray(rows, np.uint16).view(np.int16)).to(logits.device).view(torch.bfloat16)
+    flat.index_copy_(0, idx, src)
+
+
+def rel_err(got: np.ndarray, want: np.ndarray) -> np.ndarray:
+    with np.errstate(divide="ignore", invalid="ignore"):
+        e = np.abs(got.astype(np.float64) - want) / np.abs(want)
+    e[(got == want)] = 0.0
+    return e
+
+
+def compare_step(gpu_last: dict, rec, act_full: np.ndarray, tol: float, select=None):
+    """Element-by-element comparison of one step.  `select` optionally restricts the GPU's
+    examined list to the entries the oracle followed (boolean mask over the GPU list)."""
+    g = {k: (v[select] if select is not None else v) for k, v in gpu_last.items()}
+    np.testing.assert_array_equal(g["active"], act_full.astype(np.int32))           # bit exact
+    np.testing.assert_array_equal(g["token"], rec.token)                             # bit exact
+    ok = rec.status == 0
+    assert np.all(np.isnan(g["conf"][~ok]))
+    assert rel_err(g["p1"][ok], rec.p1[ok]).max(initial=0) <= tol
+    assert rel_err(g["conf"][ok], rec.conf[ok]).max(initial=0) <= tol
+    assert rel_err(g["tau"], rec.tau).max(initial=0) <= 1e-5
+    big = ok & (rec.p2 > 1e-30)           # p2 below that is subnormal in binary32
+    assert rel_err(g["p2"][big], rec.p2[big]).max(initial=0) <= max(tol, 2e-5)
+    with np.errstate(invalid="ignore"):
+        commit_gpu = ok & (g["conf"] >= g["tau"])
+    np.testing.assert_array_equal(commit_gpu, rec.commit)

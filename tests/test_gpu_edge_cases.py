@@ -1,0 +1,246 @@
+"""GPU edge cases against the oracle: ragged vocabularies and strides, rows split into pieces,
+ties across pieces, -inf / NaN / +inf logits, empty and tiny canvases, many batch rows,
+extreme window radii, determinism."""
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from gen.bf16 import bf16_bits_to_f32, f32_to_bf16_bits  # noqa: E402
+from harness import GUARD  # noqa: E402
+from oracle import jot_oracle as O  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need the MI355X; there is no CPU fallback")
+    import gpu_harness
+    return gpu_harness
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def clear_guard_band(st: O.OracleState, logits: np.ndarray):
+    """Adjust the INPUT until no examined position sits within the guard band of its threshold:
+    raise that row's current argmax logit by one."""
+    p = st.params
+    flat = logits.reshape(p.B * p.L, p.V)
+    for _ in range(100):
+        act = st.active_list()
+        rec = st.evaluate(as_rows(flat[act], p.dtype))
+        with np.errstate(invalid="ignore"):
+            near = (rec.status == 0) & (np.abs(rec.conf - rec.tau) < GUARD * np.maximum(1, np.abs(rec.tau)))
+        if not near.any():
+            return
+        for k in np.flatnonzero(near):
+            v = np.float32(flat[act[k], rec.token[k]] + 1.0)
+            if p.dtype == O.BF16:
+                v = bf16_bits_to_f32(f32_to_bf16_bits(np.array([v], np.float32)))[0]
+                if v == flat[act[k], rec.token[k]]:
+                    v = np.float32(v * 2 if v > 0 else 1.0)
+            flat[act[k], rec.token[k]] = v
+    raise AssertionError("guard band not cleared")
+
+
+def as_rows(x, dtype):
+    return np.ascontiguousarray(x, np.float32) if dtype == O.F32 else f32_to_bf16_bits(np.asarray(x, np.float32))
+
+
+def to_device(logits: np.ndarray, dtype: int, stride_l: int):
+    """[B, L, V] host array -> device tensor with row stride stride_l >= V (padding = NaN)."""
+    B, L, V = logits.shape
+    tdt = torch.float32 if dtype == O.F32 else torch.bfloat16
+    dev = torch.full((B, L, stride_l), float("nan"), dtype=tdt, device="cuda")
+    dev[:, :, :V] = torch.from_numpy(logits).to("cuda").to(tdt)
+    return dev
+
+
+def check_case(gpu, p: O.OracleParams, tokens, masked, logit_seq, stride_pad=0, tol=None, clear=True):
+    import paper_2602_11133_amd as J
+    esz = 4 if p.dtype == O.F32 else 2
+    align = 16 // esz
+    stride_l = (p.V + align - 1) // align * align + stride_pad * align
+    jp = J.JotParams(B=p.B, L=p.L, V=p.V, dtype=p.dtype, conf_mode=p.conf_mode, tau_max=p.tau_max,
+                     tau_min=p.tau_min, gamma=p.gamma, D=p.D, eps=p.eps, gen_start=p.gen_start,
+                     block_size=p.block_size)
+    # the library holds gamma, tau and eps as binary32: give the oracle the same real numbers
+    p = O.OracleParams(**{**p.__dict__, "gamma": float(np.float32(p.gamma)), "tau_max": float(np.float32(p.tau_max)),
+                          "tau_min": float(np.float32(p.tau_min)), "eps": float(np.float32(p.eps))})
+    st = O.OracleState.init(p, tokens, masked)
+    g = gpu.GpuJot(jp, tokens, masked)
+    tol = tol or (1e-5 if p.dtype == O.F32 else 2e-3)
+    np.testing.assert_array_equal(g.active_list(), st.active_list().astype(np.int32))
+    for n, logits in enumerate(logit_seq, 1):
+        logits = np.array(logits, np.float32)
+        if p.dtype == O.BF16:
+            logits = bf16_bits_to_f32(f32_to_bf16_bits(logits)).reshape(logits.shape)
+        if clear:
+            clear_guard_band(st, logits)
+            if p.dtype == O.BF16:
+                assert np.array_equal(bf16_bits_to_f32(f32_to_bf16_bits(logits)).reshape(logits.shape), logits)
+        act = st.active_list()
+        rec = st.step(as_rows(logits.reshape(p.B * p.L, p.V)[act], p.dtype))
+        dev = to_device(logits, p.dtype, stride_l)
+        g.step(dev, stride_b=p.L * stride_l, stride_l=stride_l)
+        gpu.compare_step(g.last(), rec, act, tol)
+        np.testing.assert_array_equal(g.tokens(), st.tokens)
+        np.testing.assert_array_equal(g.masked(), st.masked)
+        np.testing.assert_array_equal(g.active_list(), st.active_list().astype(np.int32))
+        assert g.active_count() == st.active_count()
+        assert J.jot_anomaly_count(g.h) == st.anomalies
+        assert J.jot_step_index(g.h) == n
+    want = np.array(st.commit_log, np.int32).reshape(-1, 3)
+    np.testing.assert_array_equal(g.commit_log(), want)
+    out = (g.tokens(), g.masked(), g.commit_log(), g.last())
+    g.close()
+    return out
+
+
+def random_case(seed, B, L, V, gs, dtype=O.F32, steps=3, scale=3.0, **kw):
+    rng = np.random.default_rng(seed)
+    p = O.OracleParams(B=B, L=L, V=V, dtype=dtype, gen_start=gs, **kw)
+    masked = np.zeros((B, L), bool)
+    masked[:, gs:] = rng.random((B, L - gs)) < 0.85
+    tokens = rng.integers(0, V, (B, L)).astype(np.int32)
+    seq = []
+    target = rng.integers(0, V, (B, L))
+    for n in range(steps):
+        lg = (rng.standard_normal((B, L, V)) * scale).astype(np.float32)
+        boost = rng.uniform(0, 14, (B, L)).astype(np.float32) * (n + 1) / steps
+        np.put_along_axis(lg, target[..., None], boost[..., None] + 6.0, -1)
+        seq.append(lg)
+    return p, tokens, masked, seq
+
+
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+@pytest.mark.parametrize("V", [2, 3, 7, 8, 9, 1003, 2048, 2049, 8191, 20011])
+def test_ragged_vocabulary_and_padded_strides(gpu, dtype, V):
+    say(f"[edge] ragged V={V} dtype={dtype}")
+    p, tokens, masked, seq = random_case(V, B=2, L=37, V=V, gs=5, dtype=dtype, conf_mode=O.CONF_RATIO,
+                                         tau_max=20.0, tau_min=1.0, gamma=0.5, D=4)
+    check_case(gpu, p, tokens, masked, seq, stride_pad=1)
+
+
+@pytest.mark.parametrize("mode,tau_max,tau_min", [(O.CONF_RATIO, 90.0, 1.0), (O.CONF_MAXPROB, 0.9, 0.0),
+                                                   (O.CONF_PROBGAP, 0.8, 0.1)])
+@pytest.mark.parametrize("gamma,D", [(0.5, 8), (0.3, 4), (0.9, 16), (1.0, 32), (0.7, 1), (0.5, 0)])
+def test_spatial_parameters(gpu, mode, tau_max, tau_min, gamma, D):
+    say(f"[edge] spatial mode={mode} gamma={gamma} D={D}")
+    p, tokens, masked, seq = random_case(D * 7 + mode, B=3, L=131, V=512, gs=40, conf_mode=mode,
+                                         tau_max=tau_max, tau_min=tau_min, gamma=gamma, D=D, steps=4)
+    check_case(gpu, p, tokens, masked, seq)
+
+
+@pytest.mark.parametrize("block", [1, 5, 32, 64, 500])
+def test_block_mode(gpu, block):
+    say(f"[edge] block={block}")
+    p, tokens, masked, seq = random_case(block, B=4, L=200, V=300, gs=30, conf_mode=O.CONF_MAXPROB,
+                                         tau_max=0.7, tau_min=0.0, gamma=0.5, D=8, block_size=block, steps=8)
+    masked[1, 10:20] = True          # masked positions inside the prompt region too
+    check_case(gpu, p, tokens, masked, seq)
+
+
+def test_rows_split_into_pieces_with_ties_across_pieces(gpu):
+    # few examined rows and a long vocabulary: each row is cut into several pieces that are
+    # merged afterwards; equal maxima sit in different pieces
+    B, L, V = 1, 6, 100_003
+    rng = np.random.default_rng(9)
+    p = O.OracleParams(B=B, L=L, V=V, dtype=O.F32, conf_mode=O.CONF_RATIO, tau_max=5.0, tau_min=0.5,
+                       gamma=0.5, D=2, gen_start=1)
+    masked = np.array([[False, True, True, True, True, True]])
+    tokens = np.zeros((B, L), np.int32)
+    lg = rng.standard_normal((B, L, V)).astype(np.float32)
+    lg[0, 1, [99_999, 50_000, 123]] = 9.0          # three-way tie: index 123 wins, m2 = m1
+    lg[0, 2, 77_777] = 12.0                        # clear winner in a late piece
+    lg[0, 2, 3] = 11.0                             # runner-up in the first piece
+    lg[0, 3, V - 1] = 15.0                         # winner in the ragged tail
+    lg[0, 4, :] = -np.inf
+    lg[0, 4, 60_000] = 0.0                         # a single finite entry: p1 = 1, p2 = 0
+    lg[0, 5, 0] = 10.0
+    lg[0, 5, 1] = 10.0                             # tie inside one vector
+    toks, msk, log, last = check_case(gpu, p, tokens, masked, [lg], clear=False)
+    assert last["token"].tolist() == [123, 77_777, V - 1, 60_000, 0]
+    assert last["p2"][3] == 0.0 and last["p1"][3] == 1.0
+
+
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+def test_rows_without_softmax_and_minus_inf_entries(gpu, dtype):
+    B, L, V = 2, 12, 5000
+    rng = np.random.default_rng(4)
+    p = O.OracleParams(B=B, L=L, V=V, dtype=dtype, conf_mode=O.CONF_MAXPROB, tau_max=0.5, tau_min=0.0,
+                       gamma=0.5, D=3, gen_start=2)
+    masked = np.zeros((B, L), bool)
+    masked[:, 2:] = True
+    lg = rng.standard_normal((B, L, V)).astype(np.float32)
+    lg[:, :, 17] = 14.0                              # everything would finalize ...
+    lg[0, 3, 4000] = np.nan                          # ... except rows without a softmax
+    lg[0, 4, 99] = np.inf
+    lg[0, 5, :] = -np.inf
+    lg[1, 6, ::2] = -np.inf                          # masked-out tokens are fine
+    lg[1, 7, :] = -200.0                             # very negative everywhere: shift invariance
+    lg[1, 7, 17] = -190.0
+    lg[1, 8, :] = 3.0e4 if dtype == O.F32 else 3.0e4  # huge but finite
+    lg[1, 8, 17] = 3.0e4 + 64
+    toks, msk, log, last = check_case(gpu, p, np.zeros((B, L), np.int32), masked, [lg, lg], clear=False)
+    assert msk[0, 3] and msk[0, 4] and msk[0, 5]
+    assert not msk[1, 6] and not msk[1, 7] and not msk[1, 8]
+
+
+def test_empty_and_tiny_canvases(gpu):
+    import paper_2602_11133_amd as J
+    # nothing masked: zero examined positions, steps are no-ops
+    p = O.OracleParams(B=2, L=5, V=16, gen_start=5)
+    tokens = np.arange(10, dtype=np.int32).reshape(2, 5)
+    masked = np.zeros((2, 5), bool)
+    lg = np.zeros((2, 5, 16), np.float32)
+    toks, msk, log, last = check_case(gpu, p, tokens, masked, [lg, lg], clear=False)
+    assert log.shape == (0, 3) and last["active"].size == 0
+    np.testing.assert_array_equal(toks, tokens)
+    # one position, two tokens
+    p = O.OracleParams(B=1, L=1, V=2, conf_mode=O.CONF_RATIO, tau_max=3.0, tau_min=1.0, D=8)
+    lg = np.array([[[0.0, 2.0]]], np.float32)
+    toks, msk, log, last = check_case(gpu, p, np.zeros((1, 1), np.int32), np.ones((1, 1), bool), [lg])
+    assert toks[0, 0] == 1 and log.tolist() == [[1, 0, 1]]
+
+
+def test_many_batch_rows(gpu):
+    # more batch rows than threads in a workgroup: the prefix over rows takes several strides
+    p, tokens, masked, seq = random_case(31, B=700, L=9, V=40, gs=2, conf_mode=O.CONF_MAXPROB,
+                                         tau_max=0.6, tau_min=0.0, gamma=0.5, D=2, steps=3)
+    check_case(gpu, p, tokens, masked, seq)
+
+
+def test_long_rows_cross_word_boundaries(gpu):
+    # L not a multiple of 64 or 256; windows straddle 64-bit words of the mask image
+    p, tokens, masked, seq = random_case(12, B=2, L=333, V=64, gs=61, conf_mode=O.CONF_RATIO,
+                                         tau_max=40.0, tau_min=1.0, gamma=0.9, D=32, steps=5)
+    check_case(gpu, p, tokens, masked, seq)
+
+
+def test_bf16_ties_are_broken_by_lowest_index(gpu):
+    B, L, V = 1, 40, 30_000
+    rng = np.random.default_rng(8)
+    p = O.OracleParams(B=B, L=L, V=V, dtype=O.BF16, conf_mode=O.CONF_RATIO, tau_max=1.0, tau_min=0.5,
+                       gamma=0.5, D=8, gen_start=0)
+    masked = np.ones((B, L), bool)
+    lg = np.round(rng.standard_normal((B, L, V)) * 2).astype(np.float32)     # integers: many ties at the top
+    toks, msk, log, last = check_case(gpu, p, np.zeros((B, L), np.int32), masked, [lg], clear=False)
+    assert np.array_equal(last["token"], np.argmax(lg[0], -1))
+
+
+def test_two_runs_are_bitwise_identical(gpu):
+    p, tokens, masked, seq = random_case(77, B=3, L=90, V=9000, gs=10, dtype=O.BF16, conf_mode=O.CONF_RATIO,
+                                         tau_max=30.0, tau_min=1.0, gamma=0.5, D=8, steps=4)
+    a = check_case(gpu, p, tokens, masked, seq)
+    b = check_case(gpu, p, tokens, masked, seq)
+    for x, y in zip(a[:3], b[:3]):
+        np.testing.assert_array_equal(x, y)
+    for k in a[3]:
+        np.testing.assert_array_equal(a[3][k].view(np.uint32), b[3][k].view(np.uint32))

@@ -1,0 +1,174 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI.
+
+Bar: bit-exact argmax tokens, masks, commit order and active lists; confidences within 1e-5
+relative for fp32 logits and 2e-3 relative for bf16 logits.  Every confidence of the oracle is
+kept at least 1e-4 (relative to max(1, tau)) away from its threshold by the input recipe, so
+the fp32 decision on the GPU and the fp64 decision of the oracle are the same decision.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from gen.configs import BF16, CONF_MAXPROB, CONF_PROBGAP, CONF_RATIO, CONFIGS, F32  # noqa: E402
+from harness import LockstepRun  # noqa: E402
+
+THREADS = int(os.environ.get("JOT_TEST_THREADS", "16"))
+TOL = {F32: 1e-5, BF16: 2e-3}
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need the MI355X; there is no CPU fallback")
+    import gpu_harness
+    return gpu_harness
+
+
+def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True):
+    """Lock-step decode: oracle on the host (optionally on a subset of batch rows), library on
+    the GPU over the whole batch; compares every step and the final state."""
+    from gen.device import DeviceGenerator
+    say(f"[parity] {cfg.name} B={cfg.B} L={cfg.L} V={cfg.V} dtype={cfg.dtype} mode={cfg.conf_mode} "
+        f"tau=({cfg.tau_max},{cfg.tau_min}) block={cfg.block_size} rows={batch_rows}")
+    run = LockstepRun(cfg, threads=THREADS, batch_rows=batch_rows)
+    tokens0, masked0 = run.traj.initial_canvas()
+    g = gpu.GpuJot(gpu.params_of(cfg), tokens0, masked0)
+    dgen = DeviceGenerator(cfg, run.traj.target, run.traj.rival)
+    logits = dgen.alloc_logits(poison=True)
+    followed = np.zeros(cfg.B, bool)
+    followed[run.batch_rows] = True
+    steps = cfg.steps + 16 if max_steps is None else max_steps
+    import paper_2602_11133_amd as J
+    n_done = 0
+    for n in range(1, steps + 1):
+        if run.state.active_count() == 0:
+            break
+        act_full = run.active_full()
+        rec, T, R, rows = run.next_step()
+        n_gpu = g.active_count()
+        if use_device_gen:
+            dgen.set_planted(T, R)
+            dgen.fill(logits, n, J.jot_active_list(g.h), n_gpu)
+        else:
+            gpu.upload_rows(logits, act_full, rows, cfg.dtype)
+        g.step(logits)
+        last = g.last()
+        sel = followed[last["active"] // cfg.L] if batch_rows is not None else None
+        gpu.compare_step(last, rec, act_full, TOL[cfg.dtype], sel)
+        n_done = n
+        if n % 32 == 0:
+            say(f"  step {n}: examined {last['active'].size}, oracle rows {act_full.size}")
+    say(f"  finished after {n_done} steps, bumps={run.n_bumps}")
+    # final state of the followed rows
+    st = run.state
+    tok, msk, cst = g.tokens(), g.masked(), g.commit_step()
+    np.testing.assert_array_equal(tok[run.batch_rows], st.tokens)
+    np.testing.assert_array_equal(msk[run.batch_rows], st.masked)
+    log = g.commit_log()
+    keep = followed[log[:, 1] // cfg.L]
+    want = np.array([(s, int(run.to_full(np.array([p]))[0]), t) for (s, p, t) in st.commit_log],
+                    np.int32).reshape(-1, 3)
+    np.testing.assert_array_equal(log[keep], want)
+    # commit_step agrees with the log
+    for (s, p, t) in want[:: max(1, len(want) // 200)]:
+        assert cst.reshape(-1)[p] == s and tok.reshape(-1)[p] == t
+    if batch_rows is None:
+        np.testing.assert_array_equal(g.active_list(), run.active_full().astype(np.int32))
+    assert g.active_count() >= 0
+    g.close()
+    return n_done
+
+
+# --------------------------------------------------------------------------- generator identity
+
+@pytest.mark.parametrize("cid", [1, 2, 5])
+def test_device_generator_is_byte_identical_to_host(gpu, cid):
+    from gen.device import DeviceGenerator
+    from gen.host import HostGenerator
+    from gen.trajectory import Trajectory
+    cfg = CONFIGS[cid]
+    if cid == 5:
+        cfg = cfg.replace(B=2)
+    tr = Trajectory(cfg)
+    T, R = tr.planted(3)
+    hg = HostGenerator(cfg, tr.target, tr.rival, threads=THREADS)
+    dg = DeviceGenerator(cfg, tr.target, tr.rival)
+    dg.set_planted(T, R)
+    logits = dg.alloc_logits(poison=True)
+    pos = np.unique(np.concatenate([[cfg.gen_start, cfg.B * cfg.L - 1],
+                                    np.random.default_rng(cid).integers(cfg.gen_start, cfg.L, 20)]))
+    pos = pos[(pos % cfg.L) >= cfg.gen_start]
+    pos_dev = torch.from_numpy(pos.astype(np.int32)).cuda()
+    dg.fill(logits, 3, pos_dev.data_ptr(), pos.size)
+    torch.cuda.synchronize()
+    got = logits.view(cfg.B * cfg.L, cfg.V)[torch.from_numpy(pos).cuda()].cpu()
+    want = hg.rows(3, pos, T, R)
+    if cfg.dtype == F32:
+        np.testing.assert_array_equal(got.numpy().view(np.uint32), want.view(np.uint32))
+    else:
+        np.testing.assert_array_equal(got.view(torch.int16).numpy().view(np.uint16), want)
+    # rows that were not generated still hold the poison
+    other = cfg.gen_start + 1 if (cfg.gen_start + 1) not in pos else cfg.gen_start - 1
+    assert torch.isnan(logits.view(cfg.B * cfg.L, cfg.V)[other].float()).all()
+
+
+# --------------------------------------------------------------------------- the five workloads
+
+@pytest.mark.parametrize("mode,tau_max,tau_min", [(CONF_MAXPROB, 0.9, 0.0), (CONF_RATIO, 90.0, 1.0),
+                                                   (CONF_PROBGAP, 0.9, 0.0)])
+def test_config1_single_step(gpu, mode, tau_max, tau_min):
+    cfg = CONFIGS[1].replace(conf_mode=mode, tau_max=tau_max, tau_min=tau_min)
+    assert run_parity(gpu, cfg, max_steps=1) == 1
+
+
+def test_config1_host_uploaded_rows(gpu):
+    # same case with rows generated on the host and copied in: independent of the device generator
+    assert run_parity(gpu, CONFIGS[1], max_steps=1, use_device_gen=False) == 1
+
+
+def test_config2_full_loop(gpu):
+    run_parity(gpu, CONFIGS[2])
+
+
+@pytest.mark.parametrize("mode,tau_max,tau_min", [(CONF_RATIO, 90.0, 1.0), (CONF_PROBGAP, 0.9, 0.0)])
+def test_config2_other_signals_short(gpu, mode, tau_max, tau_min):
+    cfg = CONFIGS[2].replace(conf_mode=mode, tau_max=tau_max, tau_min=tau_min, steps=24, L=64 + 96)
+    run_parity(gpu, cfg)
+
+
+@pytest.mark.parametrize("tau_max", [0.7, 0.8, 0.9])
+def test_config3_threshold_sweep(gpu, tau_max):
+    cfg = CONFIGS[3].replace(tau_max=tau_max)
+    rows = None if tau_max == 0.9 else [0, 5]
+    run_parity(gpu, cfg, batch_rows=rows)
+
+
+def test_config4_blockwise(gpu):
+    run_parity(gpu, CONFIGS[4], batch_rows=[0, 17, 31])
+
+
+def test_config4_blockwise_ratio_llada_defaults_short(gpu):
+    cfg = CONFIGS[4].replace(conf_mode=CONF_RATIO, tau_max=30.0, tau_min=1.0, B=4, L=128 + 128, steps=128)
+    run_parity(gpu, cfg)
+
+
+def test_config5_full_size(gpu):
+    # the whole batch runs on the GPU in the launch shape the benchmark times; the oracle
+    # follows one batch row through all steps (rows are independent decodes)
+    run_parity(gpu, CONFIGS[5], batch_rows=[41])
+
+
+def test_config5_probgap_short(gpu):
+    cfg = CONFIGS[5].replace(conf_mode=CONF_PROBGAP, tau_max=0.9, tau_min=0.0, B=2, L=256 + 128,
+                             steps=32, base="partition", noise_scale=0.02)
+    run_parity(gpu, cfg)
