@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Throughput of the JoT finalization pass on one MI355X.
+
+A "step" is one jot_step() -- vocabulary reduction of every examined position, confidence,
+spatial threshold, decision, commit and compaction -- followed by the jot_active_count() a decode
+loop needs for its termination test.  The workload is the largest synthetic configuration
+(B=64, 1024 generated positions after a 256-token prompt, V=152064, fp32 logits, the paper's
+ratio signal with tau_max=90, tau_min=1, gamma=0.5, D=8), decoded from its first step; the
+logits of the timed steps are generated on the device beforehand and are resident in HBM.
+
+Prints one JSON line.  `value` = sum over timed steps of (examined positions x V) / wall time.
+`roofline` is for the vocabulary-reduction kernel (the only kernel that touches the logits):
+bytes = examined positions x V x element size, duration from HIP events around that kernel.
+`cpu_baseline` is the double-precision CPU oracle timed on this machine on a sample of the same
+step-1 rows.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+
+
+def host_threads() -> int:
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    return max(1, min(16, n))
+
+
+def load_probe():
+    from paper_2602_11133_amd import build as jb
+    if not os.path.exists(jb.PROBE_LIB):
+        raise RuntimeError(f"{jb.PROBE_LIB} is missing: run __graft_entry__.build() first")
+    lib = ctypes.CDLL(jb.PROBE_LIB)
+    vp, i64 = ctypes.c_void_p, ctypes.c_int64
+    lib.jot_probe_copy.argtypes, lib.jot_probe_copy.restype = [vp, vp, i64, vp], ctypes.c_int
+    lib.jot_probe_read.argtypes, lib.jot_probe_read.restype = [vp, i64, vp, vp], ctypes.c_int
+    return lib
+
+
+def probe_copy_only(torch, reps: int):
+    """Plain copy of 1 GiB, `reps` times: calibration target for FETCH_SIZE / WRITE_SIZE."""
+    lib = load_probe()
+    n = 1 << 30
+    src = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    st = torch.cuda.current_stream().cuda_stream
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        assert lib.jot_probe_copy(src.data_ptr(), dst.data_ptr(), n, st) == 0
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    print(json.dumps({"probe": "copy", "bytes_read_per_launch": n, "bytes_written_per_launch": n,
+                      "launches": reps, "GBps_read_plus_write": 2 * n * reps / dt / 1e9}))
+
+
+def read_ceiling(torch, buf, reps=3) -> float:
+    """Best-of-reps GB/s of a plain read-only streaming kernel over one logits buffer."""
+    lib = load_probe()
+    nbytes = buf.numel() * buf.element_size() // 32768 * 32768
+    out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    best = 0.0
+    for _ in range(reps + 1):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        assert lib.jot_probe_read(buf.data_ptr(), nbytes, out.data_ptr(), st) == 0
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    return best
+
+
+def cpu_baseline(cfg, traj, sample_rows: int):
+    """The oracle's evaluation of step 1 on the first `sample_rows` batch rows, all host threads."""
+    import numpy as np
+    from gen.host import HostGenerator
+    from harness import oracle_params
+    from oracle import jot_oracle as O
+    threads = host_threads()
+    rows_b = list(range(min(sample_rows, cfg.B)))
+    tokens, masked = traj.initial_canvas()
+    sub = cfg.replace(B=len(rows_b))
+    st = O.OracleState.init(oracle_params(sub), tokens[rows_b], masked[rows_b], threads=threads)
+    act = st.active_list()
+    T, R = traj.planted(1)
+    rows = HostGenerator(cfg, traj.target, traj.rival, threads).rows(1, act, T, R)   # untimed
+    t0 = time.perf_counter()
+    rec = st.evaluate(rows)
+    dt = time.perf_counter() - t0
+    assert rec.active.size == act.size
+    return {"value": act.size * cfg.V / dt, "unit": "positions·vocab/s", "cores": threads, "kind": "oracle",
+            "sample": f"step 1, batch rows 0-{len(rows_b) - 1} ({act.size} positions x V={cfg.V}), "
+                      f"{dt:.2f} s wall on {threads} threads", "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=5, help="workload 1-5 (default: the largest)")
+    ap.add_argument("--cpu-sample-rows", type=int, default=8, help="batch rows timed on the CPU oracle")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-ceiling", action="store_true")
+    ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
+                    help="only run the plain 1 GiB copy kernel N times (counter calibration) and exit")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the pass shards over batch rows with no "
+              "exchange; no multi-GPU figure is produced). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the finalization pass has no CPU path", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    if args.probe_copy:
+        probe_copy_only(torch, args.probe_copy)
+        return
+
+    import paper_2602_11133_amd as J
+    import gpu_harness
+    from gen.configs import CONFIGS, F32
+    from gen.device import DeviceGenerator
+    from gen.trajectory import Trajectory
+
+    cfg = CONFIGS[args.config]
+    K, W = args.steps, args.warmup
+    traj = Trajectory(cfg)
+    dgen = DeviceGenerator(cfg, traj.target, traj.rival)
+    tokens0, masked0 = traj.initial_canvas()
+    esz = cfg.elem_bytes
+    buf_bytes = cfg.B * cfg.L * cfg.V * esz
+    free, _total = torch.cuda.mem_get_info()
+    resident = int(max(1, min(K, (free * 0.85) // buf_bytes)))
+    bufs = [dgen.alloc_logits(poison=False) for _ in range(resident)]
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def fill_segment(g, first_step, count):
+        """(untimed) logits of steps first_step .. first_step+count-1 for every position that is
+        still examined when the segment starts (a superset of what each step will read)."""
+        n_act = g.active_count()
+        for k in range(count):
+            T, R = traj.planted(first_step + k)
+            dgen.set_planted(T, R)
+            dgen.fill(bufs[k], first_step + k, J.jot_active_list(g.h), n_act)
+        torch.cuda.synchronize()
+
+    def decode(g, n_steps, timed):
+        """Runs n_steps steps in segments of `resident`; returns (seconds, [A_n], [reduce ms])."""
+        total, examined, kms = 0.0, [], []
+        done = 0
+        while done < n_steps:
+            seg = min(resident, n_steps - done)
+            fill_segment(g, done + 1, seg)
+            a_prev = g.active_count()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for k in range(seg):
+                J.jot_step(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, stream)
+                a_next = J.jot_active_count(g.h)        # the decode loop's termination test
+                examined.append(a_prev)
+                a_prev = a_next
+            torch.cuda.synchronize()
+            total += time.perf_counter() - t0
+            if timed:
+                kms += [J.jot_profile_read(g.h, done + 1 + k) for k in range(seg)]
+            done += seg
+        return total, examined, kms
+
+    # warm-up on a state of its own, then a fresh state for the timed steps
+    if W > 0:
+        gw = gpu_harness.GpuJot(gpu_harness.params_of(cfg), tokens0, masked0)
+        decode(gw, W, timed=False)
+        gw.close()
+    g = gpu_harness.GpuJot(gpu_harness.params_of(cfg), tokens0, masked0)
+    J.jot_profile_enable(g.h, True)
+    seconds, examined, kms = decode(g, K, timed=True)
+    anomalies = J.jot_anomaly_count(g.h)
+    remaining = g.active_count()
+    g.close()
+
+    elems = float(sum(examined)) * cfg.V
+    value = elems / seconds
+    k_bytes = elems * esz / K                       # algorithmic bytes per launch (average)
+    k_sec = sum(kms) * 1e-3 / K                     # average launch duration
+    achieved = k_bytes / k_sec / 1e9
+    out = {
+        "metric": "active positions·vocab/s per jot_step",
+        "value": value, "unit": "positions·vocab/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": seconds / K * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if cfg.dtype == F32 else "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B}, L={cfg.L} ({cfg.gen_start} prompt + {cfg.n_gen} generated), "
+                               f"V={cfg.V}, decode steps 1..{K}", "examined_positions_per_step": examined,
+                   "conf_mode": cfg.conf_mode, "tau_max": cfg.tau_max, "tau_min": cfg.tau_min,
+                   "gamma": cfg.gamma, "D": cfg.D, "block_size": cfg.block_size,
+                   "resident_logit_buffers": resident, "still_active_after": remaining, "anomalies": anomalies},
+        "hbm_GBps_active_logits": elems * esz / seconds / 1e9,
+        "pct_of_hbm_peak": 100.0 * elems * esz / seconds / 1e9 / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "jot_vocab_reduce_kernel", "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": None, "bytes_per_launch": k_bytes, "avg_launch_ms": k_sec * 1e3,
+                     "launch_ms": kms},
+    }
+    if not args.no_ceiling:
+        out["stream_read_ceiling_GBps"] = read_ceiling(torch, bufs[0])
+    del bufs
+    torch.cuda.empty_cache()
+    if not args.no_cpu:
+        cb = cpu_baseline(cfg, traj, args.cpu_sample_rows)
+        cb["gpu_over_cpu"] = value / cb["value"]
+        out["cpu_baseline"] = cb
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -147,12 +147,14 @@ const float*   jot_last_tau(const jot_state* s);
 
 /*
  * Optional timing of the vocabulary-reduction kernel (the one that reads the logits):
- * when enabled, jot_step brackets that kernel with HIP events on `stream`.
- * jot_profile_read waits for the last step and returns the kernel's duration of that step in
- * milliseconds in *vocab_reduce_ms.
+ * when enabled, jot_step brackets that kernel with HIP events on `stream`; the events of the
+ * last JOT_PROFILE_RING steps are kept.  jot_profile_read waits for step `step` (1-based, one of
+ * the last JOT_PROFILE_RING steps enqueued while profiling was on) and returns that kernel's
+ * duration in milliseconds in *vocab_reduce_ms.
  */
+#define JOT_PROFILE_RING 64
 int jot_profile_enable(jot_state* s, int on);
-int jot_profile_read(jot_state* s, float* vocab_reduce_ms);
+int jot_profile_read(jot_state* s, int32_t step, float* vocab_reduce_ms);
 
 /* Free the host object and its pinned host counters (device memory is the caller's). */
 void jot_release(jot_state* s);

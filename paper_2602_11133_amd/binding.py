@@ -73,7 +73,7 @@ def load_library():
         "jot_last_token": (vp, [vp]), "jot_last_conf": (vp, [vp]), "jot_last_p1": (vp, [vp]),
         "jot_last_p2": (vp, [vp]), "jot_last_tau": (vp, [vp]),
         "jot_profile_enable": (ctypes.c_int, [vp, ctypes.c_int]),
-        "jot_profile_read": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_float)]),
+        "jot_profile_read": (ctypes.c_int, [vp, i32, ctypes.POINTER(ctypes.c_float)]),
         "jot_release": (None, [vp]),
         "jot_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     }
@@ -164,9 +164,10 @@ def jot_profile_enable(s: int, on: bool) -> None:
     _check(load_library().jot_profile_enable(s, int(bool(on))), "jot_profile_enable")
 
 
-def jot_profile_read(s: int) -> float:
+def jot_profile_read(s: int, step: int) -> float:
+    """Milliseconds the vocabulary-reduction kernel of step `step` took."""
     ms = ctypes.c_float()
-    _check(load_library().jot_profile_read(s, ctypes.byref(ms)), "jot_profile_read")
+    _check(load_library().jot_profile_read(s, int(step), ctypes.byref(ms)), "jot_profile_read")
     return ms.value
 
 

@@ -5,6 +5,8 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "_lib", "libjot.so")
+PROBE_LIB = os.path.join(_HERE, "_lib", "libjot_probe.so")
+PROBE_SRC = os.path.join(CSRC, "jot_probe.hip")
 SOURCES = ["jot_api.hip"]
 HEADERS = ["jot_device.h", "jot_vocab_reduce.h", "jot_decide.h", "jot_compact.h",
            os.path.join("..", "..", "include", "jot.h")]
@@ -29,5 +31,14 @@ def build(force: bool = False, extra_flags=()) -> str:
     return LIB
 
 
+def build_probe(force: bool = False) -> str:
+    """Measurement kernels (plain copy / plain read), used by bench.py only."""
+    if force or not os.path.exists(PROBE_LIB) or os.path.getmtime(PROBE_LIB) < os.path.getmtime(PROBE_SRC):
+        os.makedirs(os.path.dirname(PROBE_LIB), exist_ok=True)
+        subprocess.check_call(["hipcc", *HIPCC_FLAGS, "-o", PROBE_LIB, PROBE_SRC])
+    return PROBE_LIB
+
+
 if __name__ == "__main__":
     print(build(force=True))
+    print(build_probe(force=True))

@@ -104,8 +104,8 @@ struct jot_state {
     hipEvent_t done;
     bool have_done;
     bool profile;
-    hipEvent_t prof0, prof1;
-    bool prof_valid;
+    hipEvent_t prof0[JOT_PROFILE_RING], prof1[JOT_PROFILE_RING];
+    int32_t prof_step[JOT_PROFILE_RING];    // step recorded in each ring slot, 0 = none
 
     template <class T> T* at(int64_t off) const { return reinterpret_cast<T*>(ws + off); }
     int32_t* active(int which) const { return at<int32_t>(which ? lay.active1 : lay.active0); }
@@ -193,7 +193,6 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
     s->step = 0;
     s->have_done = false;
     s->profile = false;
-    s->prof_valid = false;
     s->host = nullptr;
 
     JotDecideParams& d = s->decide;
@@ -257,7 +256,11 @@ int jot_step(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t str
     const int in = s->cur;
     const int64_t n = (int64_t)p.B * p.L;
 
-    if (s->profile && hipEventRecord(s->prof0, st) != hipSuccess) return JOT_ERR_HIP;
+    const int slot = step % JOT_PROFILE_RING;
+    if (s->profile) {
+        s->prof_step[slot] = 0;
+        if (hipEventRecord(s->prof0[slot], st) != hipSuccess) return JOT_ERR_HIP;
+    }
     if (p.dtype == JOT_F32)
         hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotF32>, dim3(s->grid_reduce), dim3(JOT_WG), 0, st,
                            logits_dev, stride_b, stride_l, p.L, p.V, s->active(in), s->counters(in),
@@ -268,8 +271,8 @@ int jot_step(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t str
                            s->at<JotPartial>(s->lay.partials), s->target_items);
     if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     if (s->profile) {
-        if (hipEventRecord(s->prof1, st) != hipSuccess) return JOT_ERR_HIP;
-        s->prof_valid = true;
+        if (hipEventRecord(s->prof1[slot], st) != hipSuccess) return JOT_ERR_HIP;
+        s->prof_step[slot] = step;
     }
 
     hipLaunchKernelGGL(jot_decide_kernel, dim3((unsigned)((n + JOT_WG - 1) / JOT_WG)), dim3(JOT_WG), 0, st,
@@ -327,35 +330,37 @@ int jot_profile_enable(jot_state* s, int on)
 {
     if (!s) return JOT_ERR_NULL_POINTER;
     if (on && !s->profile) {
-        if (hipEventCreate(&s->prof0) != hipSuccess) return JOT_ERR_HIP;
-        if (hipEventCreate(&s->prof1) != hipSuccess) { (void)hipEventDestroy(s->prof0); return JOT_ERR_HIP; }
+        for (int k = 0; k < JOT_PROFILE_RING; ++k) {
+            s->prof_step[k] = 0;
+            if (hipEventCreate(&s->prof0[k]) != hipSuccess || hipEventCreate(&s->prof1[k]) != hipSuccess)
+                return JOT_ERR_HIP;
+        }
         s->profile = true;
-        s->prof_valid = false;
     } else if (!on && s->profile) {
-        (void)hipEventDestroy(s->prof0);
-        (void)hipEventDestroy(s->prof1);
+        for (int k = 0; k < JOT_PROFILE_RING; ++k) {
+            (void)hipEventDestroy(s->prof0[k]);
+            (void)hipEventDestroy(s->prof1[k]);
+        }
         s->profile = false;
-        s->prof_valid = false;
     }
     return JOT_OK;
 }
 
-int jot_profile_read(jot_state* s, float* vocab_reduce_ms)
+int jot_profile_read(jot_state* s, int32_t step, float* vocab_reduce_ms)
 {
     if (!s || !vocab_reduce_ms) return JOT_ERR_NULL_POINTER;
-    if (!s->profile || !s->prof_valid) return JOT_ERR_INVALID_ARG;
-    if (hipEventSynchronize(s->prof1) != hipSuccess) return JOT_ERR_HIP;
-    if (hipEventElapsedTime(vocab_reduce_ms, s->prof0, s->prof1) != hipSuccess) return JOT_ERR_HIP;
+    if (!s->profile || step < 1) return JOT_ERR_INVALID_ARG;
+    const int slot = step % JOT_PROFILE_RING;
+    if (s->prof_step[slot] != step) return JOT_ERR_INVALID_ARG;
+    if (hipEventSynchronize(s->prof1[slot]) != hipSuccess) return JOT_ERR_HIP;
+    if (hipEventElapsedTime(vocab_reduce_ms, s->prof0[slot], s->prof1[slot]) != hipSuccess) return JOT_ERR_HIP;
     return JOT_OK;
 }
 
 void jot_release(jot_state* s)
 {
     if (!s) return;
-    if (s->profile) {
-        (void)hipEventDestroy(s->prof0);
-        (void)hipEventDestroy(s->prof1);
-    }
+    if (s->profile) (void)jot_profile_enable(s, 0);
     (void)hipEventDestroy(s->done);
     if (s->host) (void)hipHostFree(s->host);
     delete s;
