@@ -41,6 +41,9 @@ __global__ __launch_bounds__(JOT_WG) void jot_decide_kernel(
     for (int j = 1; j < sp.S; ++j)
         jot_merge(m1, idx, m2, M, s, q[j].m1, q[j].idx, q[j].m2, q[j].M, q[j].s);
 
+    if (m1 == -INFINITY)
+        idx = 0;            // every logit is -inf: all are equal, the smallest index is 0
+
     // ---- probabilities: S = sum_v exp(l_v - m1) = s * 2^(M - m1*log2 e); p1 = 1/S, p2 = e^(m2-m1)/S
     const float S = s * exp2f(fmaf(-m1, JOT_LOG2E, M));
     const bool has_softmax = (S >= 0.5f) && (S < INFINITY) && (m1 < INFINITY);   // false for NaN

@@ -227,7 +227,7 @@ def test_long_rows_cross_word_boundaries(gpu):
 def test_bf16_ties_are_broken_by_lowest_index(gpu):
     B, L, V = 1, 40, 30_000
     rng = np.random.default_rng(8)
-    p = O.OracleParams(B=B, L=L, V=V, dtype=O.BF16, conf_mode=O.CONF_RATIO, tau_max=1.0, tau_min=0.5,
+    p = O.OracleParams(B=B, L=L, V=V, dtype=O.BF16, conf_mode=O.CONF_RATIO, tau_max=0.9, tau_min=0.5,
                        gamma=0.5, D=8, gen_start=0)
     masked = np.ones((B, L), bool)
     lg = np.round(rng.standard_normal((B, L, V)) * 2).astype(np.float32)     # integers: many ties at the top
