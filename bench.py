@@ -133,6 +133,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=5, help="workload 1-5 (default: the largest)")
     ap.add_argument("--cpu-sample-rows", type=int, default=16, help="batch rows timed on the CPU oracle")
+    ap.add_argument("--dtype", choices=["f32", "bf16"], default=None,
+                    help="override the logit type of the workload (changes the workload: for tuning)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
@@ -160,6 +162,8 @@ def main():
     from gen.trajectory import Trajectory
 
     cfg = CONFIGS[args.config]
+    if args.dtype is not None:
+        cfg = cfg.replace(dtype=0 if args.dtype == "f32" else 1, name=cfg.name + "_as_" + args.dtype)
     K, W = args.steps, args.warmup
     traj = Trajectory(cfg)
     dgen = DeviceGenerator(cfg, traj.target, traj.rival)
@@ -235,7 +239,7 @@ def main():
         "pct_of_hbm_peak": 100.0 * elems * esz / seconds / 1e9 / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "kernel": "jot_vocab_reduce_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": measured_traffic(args.config, K), "bytes_per_launch": k_bytes, "avg_launch_ms": k_sec * 1e3,
+                     "traffic": measured_traffic(args.config, K) if args.dtype is None else None, "bytes_per_launch": k_bytes, "avg_launch_ms": k_sec * 1e3,
                      "launch_ms": kms},
     }
     if not args.no_ceiling:

@@ -22,7 +22,8 @@ inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 // Persistent grid of the vocabulary reduction: workgroups per compute unit, and how many work
 // items a step aims for (rows are split into pieces when fewer rows than that are examined).
-constexpr int kWgPerCu = 8;
+constexpr int kDefaultWgPerCu = 4;
+constexpr int kMaxWgPerCu = 16;
 constexpr int kFallbackCus = 256;
 constexpr int kItemsPerWg = 4;
 
@@ -51,7 +52,7 @@ int validate(const jot_params* p)
     return JOT_OK;
 }
 
-int max_target_items() { return 4096 * kWgPerCu * kItemsPerWg; }   // bound used for sizing only
+int max_target_items() { return 2048 * kMaxWgPerCu * kItemsPerWg; }   // bound used for sizing only
 
 Layout make_layout(const jot_params* p, int target_items)
 {
@@ -83,10 +84,7 @@ Layout make_layout(const jot_params* p, int target_items)
     return l;
 }
 
-struct HostCounters {
-    JotCounters c;
-    unsigned long long anomalies;
-};
+using HostCounters = JotHostBlock;
 
 }  // namespace
 
@@ -100,7 +98,8 @@ struct jot_state {
     int target_items;
     JotDecideParams decide;
     JotCompactParams compact;
-    HostCounters* host;         // pinned
+    HostCounters* host;         // pinned, mapped into the device address space
+    HostCounters* host_dev;     // the device-side address of the same block
     hipEvent_t done;
     bool have_done;
     bool profile;
@@ -126,14 +125,10 @@ int enqueue_compaction(jot_state* s, int32_t step, hipStream_t st)
                        s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.row_block),
                        s->at<int32_t>(s->lay.row_n_active), s->at<int32_t>(s->lay.row_n_commit),
                        s->counters(in), s->counters(out), s->active(out),
-                       s->at<int32_t>(s->lay.commit_log), s->at<uint64_t>(s->lay.resolved_bits));
+                       s->at<int32_t>(s->lay.commit_log), s->at<uint64_t>(s->lay.resolved_bits),
+                       s->at<unsigned long long>(s->lay.anomalies), s->host_dev);
     if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
-    // counters of the new state -> pinned host memory, then the event the host waits on
-    if (hipMemcpyAsync(&s->host->c, s->counters(out), sizeof(JotCounters), hipMemcpyDeviceToHost, st) != hipSuccess)
-        return JOT_ERR_HIP;
-    if (hipMemcpyAsync(&s->host->anomalies, s->at<unsigned long long>(s->lay.anomalies), 8,
-                       hipMemcpyDeviceToHost, st) != hipSuccess)
-        return JOT_ERR_HIP;
+    // the kernel above also wrote the new counters into pinned host memory; the host waits on this
     if (hipEventRecord(s->done, st) != hipSuccess) return JOT_ERR_HIP;
     s->have_done = true;
     s->cur = out;
@@ -175,17 +170,24 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
         cus = kFallbackCus;
-    if (cus > 4096) cus = 4096;
+    if (cus > 2048) cus = 2048;
 
     jot_state* s = new (std::nothrow) jot_state();
     if (!s) return JOT_ERR_INVALID_ARG;
     s->p = *p;
     s->ws = static_cast<char*>(workspace_dev);
-    s->grid_reduce = cus * kWgPerCu;
+    // persistent grid = exactly the workgroups that can be resident at once
+    int occ = 0;
+    const void* kfn = p->dtype == JOT_F32 ? reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotF32>)
+                                          : reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotBF16>);
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kfn, JOT_WG, 0) != hipSuccess || occ < 1)
+        occ = kDefaultWgPerCu;
+    if (occ > kMaxWgPerCu) occ = kMaxWgPerCu;
     if (const char* e = getenv("JOT_REDUCE_WG_PER_CU")) {        // tuning aid, 1..16
         const int v = atoi(e);
-        if (v >= 1 && v <= 16) s->grid_reduce = cus * v;
+        if (v >= 1 && v <= kMaxWgPerCu) occ = v;
     }
+    s->grid_reduce = cus * occ;
     s->target_items = s->grid_reduce * kItemsPerWg;
     if (s->target_items > max_target_items()) s->target_items = max_target_items();
     s->lay = make_layout(p, max_target_items());
@@ -212,11 +214,16 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
     s->compact.gen_start = p->gen_start; s->compact.block_size = p->block_size;
     s->compact.words_per_row = s->lay.words_per_row;
 
-    if (hipHostMalloc(reinterpret_cast<void**>(&s->host), sizeof(HostCounters), hipHostMallocDefault) != hipSuccess) {
+    if (hipHostMalloc(reinterpret_cast<void**>(&s->host), sizeof(HostCounters), hipHostMallocMapped) != hipSuccess) {
         delete s;
         return JOT_ERR_HIP;
     }
     memset(s->host, 0, sizeof(HostCounters));
+    if (hipHostGetDevicePointer(reinterpret_cast<void**>(&s->host_dev), s->host, 0) != hipSuccess) {
+        (void)hipHostFree(s->host);
+        delete s;
+        return JOT_ERR_HIP;
+    }
     if (hipEventCreateWithFlags(&s->done, hipEventDisableTiming) != hipSuccess) {
         (void)hipHostFree(s->host);
         delete s;

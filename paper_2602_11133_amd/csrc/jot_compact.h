@@ -96,7 +96,8 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
     const int32_t* __restrict__ row_block, const int32_t* __restrict__ row_n_active,
     const int32_t* __restrict__ row_n_commit, const JotCounters* __restrict__ cnt_in,
     JotCounters* __restrict__ cnt_out, int32_t* __restrict__ active_out,
-    int32_t* __restrict__ commit_log, uint64_t* __restrict__ resolved_bits)
+    int32_t* __restrict__ commit_log, uint64_t* __restrict__ resolved_bits,
+    const unsigned long long* __restrict__ anomalies, JotHostBlock* __restrict__ host_out)
 {
     __shared__ int lds[JOT_WAVES];
     __shared__ int wave_act[JOT_WAVES], wave_com[JOT_WAVES];
@@ -159,6 +160,14 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
         cnt_out->n_log = log_base + run_com;
         cnt_out->n_examined = cnt_in->n_active;
         cnt_out->reserved = 0;
+        // the same numbers straight into pinned host memory: the host reads them after waiting
+        // for the event recorded behind this kernel, so no copy command is needed
+        host_out->c.n_active = act_base + run_act;
+        host_out->c.n_log = log_base + run_com;
+        host_out->c.n_examined = cnt_in->n_active;
+        host_out->c.reserved = 0;
+        host_out->anomalies = *anomalies;
+        __threadfence_system();
     }
 }
 

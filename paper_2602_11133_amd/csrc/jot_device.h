@@ -5,7 +5,8 @@
 
 #define JOT_WG 256                 // threads per workgroup of every kernel here (4 waves)
 #define JOT_WAVES (JOT_WG / 64)
-#define JOT_CHUNK_ALIGN 2048       // vocabulary split points are multiples of this many elements
+#define JOT_CHUNK_ALIGN 8192       // vocabulary split points are multiples of this many elements
+                                   // (= 256 threads x one whole batch of 16-byte vectors, both types)
 #define JOT_MIN_CHUNK 8192         // never split a row into pieces smaller than this
 #define JOT_MAX_D 32
 
@@ -54,6 +55,12 @@ struct JotCounters {
     int64_t n_log;        // commit-log triples written so far
     int64_t n_examined;   // positions the last step examined
     int64_t reserved;
+};
+
+// Block the last compaction workgroup writes into host-visible pinned memory.
+struct JotHostBlock {
+    JotCounters c;
+    unsigned long long anomalies;
 };
 
 #define JOT_LOG2E 1.44269504088896340736f

@@ -18,7 +18,8 @@ typedef uint32_t jot_u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte
 
 struct JotLane {
     float m1, m2;
-    int32_t idx;
+    int32_t best_vec;   // index (within the piece) of the 16-byte vector that first reached m1, -1 = none
+    jot_u32x4 best_raw; // that vector's raw contents: the element index is resolved from it at the end
     float M;            // integer-valued reference of the base-2 exponentials, -inf until set
     float s0, s1, s2, s3;
 };
@@ -27,22 +28,31 @@ __device__ __forceinline__ void jot_lane_init(JotLane& a)
 {
     a.m1 = -INFINITY;
     a.m2 = -INFINITY;
-    a.idx = 0x7fffffff;
+    a.best_vec = -1;
+    a.best_raw = (jot_u32x4)(0u);
     a.M = -INFINITY;
     a.s0 = a.s1 = a.s2 = a.s3 = 0.0f;
 }
 
-// top-2 and argmax of the lane, N consecutive elements starting at vocabulary index vbase
+// Top-2 of the lane over the N elements of one vector.  The argmax is tracked per VECTOR: if
+// some element is strictly larger than the lane maximum so far, remember the vector (index and
+// raw bits); which element it was is found once, after the loop.  Strict comparison keeps the
+// first of equal maxima, because a lane meets its vectors in ascending index order.
 template <int N>
-__device__ __forceinline__ void jot_top2(JotLane& a, const float (&x)[N], int vbase)
+__device__ __forceinline__ void jot_top2(JotLane& a, const float (&x)[N], const jot_u32x4& raw, int vec_index)
 {
+    const float before = a.m1;
 #pragma unroll
     for (int k = 0; k < N; ++k) {
-        const float xv = x[k];
-        a.m2 = __builtin_amdgcn_fmed3f(a.m1, a.m2, xv);   // second of {m1, m2, x}
-        a.idx = (xv > a.m1) ? (vbase + k) : a.idx;        // strict: first maximum keeps the index
-        a.m1 = fmaxf(a.m1, xv);
+        a.m2 = __builtin_amdgcn_fmed3f(a.m1, a.m2, x[k]);   // second of {m1, m2, x}
+        a.m1 = fmaxf(a.m1, x[k]);
     }
+    const bool better = a.m1 > before;
+    a.best_vec = better ? vec_index : a.best_vec;
+    a.best_raw.x = better ? raw.x : a.best_raw.x;
+    a.best_raw.y = better ? raw.y : a.best_raw.y;
+    a.best_raw.z = better ? raw.z : a.best_raw.z;
+    a.best_raw.w = better ? raw.w : a.best_raw.w;
 }
 
 // Keep every exponent l*log2(e) - M of the lane at or below 32: when the running maximum has
@@ -77,6 +87,7 @@ struct JotF32 {
     static constexpr int VEC = 4;              // elements per 16-byte vector
     static constexpr int ESZ = 4;
     static constexpr int UNROLL = 8;           // vectors in flight per thread
+    static constexpr uint32_t NEG_INF_WORD = 0xff800000u;   // one -inf
     __device__ static __forceinline__ void unpack(const jot_u32x4& w, float (&x)[VEC])
     {
         x[0] = __uint_as_float(w.x); x[1] = __uint_as_float(w.y);
@@ -92,6 +103,7 @@ struct JotBF16 {
     static constexpr int VEC = 8;
     static constexpr int ESZ = 2;
     static constexpr int UNROLL = 4;
+    static constexpr uint32_t NEG_INF_WORD = 0xff80ff80u;   // two -inf
     // a bf16 is the upper half of a binary32: widening is a shift / mask, exact
     __device__ static __forceinline__ void unpack(const jot_u32x4& w, float (&x)[VEC])
     {
@@ -139,8 +151,10 @@ __global__ __launch_bounds__(JOT_WG) void jot_vocab_reduce_kernel(
         JotLane a;
         jot_lane_init(a);
 
-        int c = tid;
-        for (; c + (U - 1) * JOT_WG < nvec; c += U * JOT_WG) {
+        // Whole batches of U vectors per thread, all loads of a batch issued before any is used.
+        int base = 0;                                          // workgroup-uniform
+        for (; base + U * JOT_WG <= nvec; base += U * JOT_WG) {
+            const int c = base + tid;
             jot_u32x4 w[U];
 #pragma unroll
             for (int u = 0; u < U; ++u)
@@ -149,35 +163,67 @@ __global__ __launch_bounds__(JOT_WG) void jot_vocab_reduce_kernel(
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 T::unpack(w[u], x[u]);
-                jot_top2<VEC>(a, x[u], v0 + (c + u * JOT_WG) * VEC);
+                jot_top2<VEC>(a, x[u], w[u], c + u * JOT_WG);
             }
             jot_rereference(a);
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 jot_expsum<VEC>(a, x[u]);
         }
-        for (; c < nvec; c += JOT_WG) {
-            const jot_u32x4 w = __builtin_nontemporal_load(p + c);
-            float x[VEC];
-            T::unpack(w, x);
-            jot_top2<VEC>(a, x, v0 + c * VEC);
+        // Ragged end of the piece: one more batch, loads beyond the end replaced by -inf (which
+        // changes neither the top-2 nor the sum).  Workgroup-uniform branch.
+        if (base < nvec) {
+            const int c = base + tid;
+            jot_u32x4 w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int cu = c + u * JOT_WG;
+                const bool in = cu < nvec;
+                const jot_u32x4 got = __builtin_nontemporal_load(p + (in ? cu : 0));
+                w[u].x = in ? got.x : T::NEG_INF_WORD;
+                w[u].y = in ? got.y : T::NEG_INF_WORD;
+                w[u].z = in ? got.z : T::NEG_INF_WORD;
+                w[u].w = in ? got.w : T::NEG_INF_WORD;
+            }
+            float x[U][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                T::unpack(w[u], x[u]);
+                jot_top2<VEC>(a, x[u], w[u], c + u * JOT_WG);
+            }
             jot_rereference(a);
-            jot_expsum<VEC>(a, x);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                jot_expsum<VEC>(a, x[u]);
+        }
+
+        // Which element of the remembered vector is the lane maximum: the first equal one.
+        int32_t idx = 0x7fffffff;
+        if (a.best_vec >= 0) {
+            float bx[VEC];
+            T::unpack(a.best_raw, bx);
+            int k_first = VEC - 1;
+#pragma unroll
+            for (int k = VEC - 2; k >= 0; --k)
+                k_first = (bx[k] == a.m1) ? k : k_first;
+            idx = v0 + a.best_vec * VEC + k_first;
         }
         {   // elements after the last whole vector (V not a multiple of VEC; last piece only)
             const int v = v0 + nvec * VEC + tid;
             if (v < v1) {
-                float x[1] = { T::scalar(row, v) };
-                jot_top2<1>(a, x, v);
+                const float xs = T::scalar(row, v);
+                a.m2 = __builtin_amdgcn_fmed3f(a.m1, a.m2, xs);
+                idx = (xs > a.m1) ? v : idx;
+                a.m1 = fmaxf(a.m1, xs);
                 jot_rereference(a);
-                jot_expsum<1>(a, x);
+                const float xa[1] = { xs };
+                jot_expsum<1>(a, xa);
             }
         }
 
         // lane -> wave
         float s = (a.s0 + a.s1) + (a.s2 + a.s3);
         float m1 = a.m1, m2 = a.m2, M = a.M;
-        int32_t idx = a.idx;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
             const float bm1 = __shfl_xor(m1, off, 64);
