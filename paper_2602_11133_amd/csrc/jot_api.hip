@@ -180,7 +180,8 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
     int occ = 0;
     const void* kfn = p->dtype == JOT_F32 ? reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotF32>)
                                           : reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotBF16>);
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kfn, JOT_WG, 0) != hipSuccess || occ < 1)
+    const int reduce_wg = p->dtype == JOT_F32 ? JotF32::WG : JotBF16::WG;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kfn, reduce_wg, 0) != hipSuccess || occ < 1)
         occ = kDefaultWgPerCu;
     if (occ > kMaxWgPerCu) occ = kMaxWgPerCu;
     if (const char* e = getenv("JOT_REDUCE_WG_PER_CU")) {        // tuning aid, 1..16
@@ -203,6 +204,8 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
     d.tau_max = p->tau_max; d.tau_min = p->tau_min; d.eps = p->eps;
     d.words_per_row = s->lay.words_per_row;
     d.target_items = s->target_items;
+    d.split_align = p->dtype == JOT_F32 ? JotF32::WG * JotF32::VEC * JotF32::UNROLL
+                                        : JotBF16::WG * JotBF16::VEC * JotBF16::UNROLL;
     float wmax = 0.0f;
     for (int k = 0; k <= JOT_MAX_D; ++k) d.gpow[k] = 0.0f;
     for (int k = 1; k <= p->D; ++k) {
@@ -269,13 +272,13 @@ int jot_step(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t str
         if (hipEventRecord(s->prof0[slot], st) != hipSuccess) return JOT_ERR_HIP;
     }
     if (p.dtype == JOT_F32)
-        hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotF32>, dim3(s->grid_reduce), dim3(JOT_WG), 0, st,
+        hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotF32>, dim3(s->grid_reduce), dim3(JotF32::WG), 0, st,
                            logits_dev, stride_b, stride_l, p.L, p.V, s->active(in), s->counters(in),
-                           s->at<JotPartial>(s->lay.partials), s->target_items);
+                           s->at<JotPartial>(s->lay.partials), s->target_items, INFINITY);
     else
-        hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotBF16>, dim3(s->grid_reduce), dim3(JOT_WG), 0, st,
+        hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotBF16>, dim3(s->grid_reduce), dim3(JotBF16::WG), 0, st,
                            logits_dev, stride_b, stride_l, p.L, p.V, s->active(in), s->counters(in),
-                           s->at<JotPartial>(s->lay.partials), s->target_items);
+                           s->at<JotPartial>(s->lay.partials), s->target_items, INFINITY);
     if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     if (s->profile) {
         if (hipEventRecord(s->prof1[slot], st) != hipSuccess) return JOT_ERR_HIP;

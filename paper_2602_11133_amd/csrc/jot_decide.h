@@ -16,6 +16,7 @@ struct JotDecideParams {
     float wmax;                   // 2 * sum_{d=1..D} gamma^d, summed in float in the order d = 1..D
     int32_t words_per_row;        // 64-bit words of the resolved-bit image per batch row
     int32_t target_items;
+    int32_t split_align;          // piece alignment of the vocabulary reduction (elements)
     float gpow[JOT_MAX_D + 1];    // gpow[d] = gamma^d
 };
 
@@ -32,7 +33,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_decide_kernel(
     const int64_t r = (int64_t)blockIdx.x * JOT_WG + threadIdx.x;
     if (r >= n_active)
         return;
-    const JotSplit sp = jot_plan_split(n_active, prm.V, prm.target_items);
+    const JotSplit sp = jot_plan_split(n_active, prm.V, prm.target_items, prm.split_align);
 
     // ---- merge the pieces of the row, in piece order
     const JotPartial* q = partials + r * sp.S;

@@ -3,11 +3,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#ifndef JOT_WG
 #define JOT_WG 256                 // threads per workgroup of every kernel here (4 waves)
+#endif
 #define JOT_WAVES (JOT_WG / 64)
-#define JOT_CHUNK_ALIGN 8192       // vocabulary split points are multiples of this many elements
-                                   // (= 256 threads x one whole batch of 16-byte vectors, both types)
-#define JOT_MIN_CHUNK 8192         // never split a row into pieces smaller than this
 #define JOT_MAX_D 32
 
 // Partial result of the vocabulary reduction over a contiguous piece of one logit row.
@@ -24,12 +23,14 @@ struct __align__(32) JotPartial {
 
 struct JotSplit {
     int S;          // pieces per row
-    int chunk;      // elements per piece (multiple of JOT_CHUNK_ALIGN unless S == 1)
+    int chunk;      // elements per piece (multiple of the alignment unless S == 1)
 };
 
 // How a step with n_active examined rows cuts each row so that the persistent grid has about
-// target_items work items.  Evaluated identically by every kernel of the step.
-__host__ __device__ inline JotSplit jot_plan_split(int64_t n_active, int V, int target_items)
+// target_items work items.  `align` = elements one workgroup of the reduction consumes per batch
+// of loads (threads x elements per vector x vectors in flight); pieces are whole batches and at
+// least one batch long.  Evaluated identically by every kernel of the step.
+__host__ __device__ inline JotSplit jot_plan_split(int64_t n_active, int V, int target_items, int align)
 {
     JotSplit sp;
     sp.S = 1;
@@ -37,13 +38,13 @@ __host__ __device__ inline JotSplit jot_plan_split(int64_t n_active, int V, int 
     if (n_active <= 0 || n_active >= target_items)
         return sp;
     int64_t want = (target_items + n_active - 1) / n_active;
-    int max_s = V / JOT_MIN_CHUNK;
+    int max_s = V / align;
     if (max_s < 1) max_s = 1;
     int s0 = want < max_s ? (int)want : max_s;
     if (s0 <= 1)
         return sp;
     int chunk = (V + s0 - 1) / s0;
-    chunk = (chunk + JOT_CHUNK_ALIGN - 1) / JOT_CHUNK_ALIGN * JOT_CHUNK_ALIGN;
+    chunk = (chunk + align - 1) / align * align;
     sp.chunk = chunk;
     sp.S = (V + chunk - 1) / chunk;
     return sp;

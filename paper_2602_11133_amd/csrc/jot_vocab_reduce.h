@@ -8,11 +8,27 @@
 // Launch shape: a persistent grid.  Work items are (examined row, piece of the row); workgroup w
 // handles items w, w + G, w + 2G, ...  The number of examined rows lives in device memory (it is
 // produced by the previous step), so the loop bound is read on the device and the launch itself
-// never depends on it.  Each of the 256 threads streams 16-byte vectors, 256 vectors apart, and
-// keeps its running state in registers; a wave-level butterfly and a 4-entry LDS exchange
-// combine the 256 lane states into one JotPartial.
+// never depends on it.  Each thread streams 16-byte vectors, one workgroup width apart, and
+// keeps its running state in registers; a wave-level butterfly and a small LDS exchange
+// combine the lane states of the workgroup into one JotPartial.
 #pragma once
 #include "jot_device.h"
+
+#ifndef JOT_F32_UNROLL
+#define JOT_F32_UNROLL 8
+#endif
+#ifndef JOT_BF16_UNROLL
+#define JOT_BF16_UNROLL 4
+#endif
+// Workgroup sizes of the reduction, chosen by measurement on MI355X: fp32 rows stream best with
+// few, large workgroups (one 1024-thread workgroup per CU, i.e. 256 rows in flight), the bf16
+// path does twice the arithmetic per byte and wants more, smaller workgroups to hide it.
+#ifndef JOT_F32_WG
+#define JOT_F32_WG 1024
+#endif
+#ifndef JOT_BF16_WG
+#define JOT_BF16_WG 256
+#endif
 
 typedef uint32_t jot_u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte load
 
@@ -34,18 +50,30 @@ __device__ __forceinline__ void jot_lane_init(JotLane& a)
     a.s0 = a.s1 = a.s2 = a.s3 = 0.0f;
 }
 
+// max(a, b) as the median of {a, b, +inf}: one v_med3_f32.  fmaxf() would spend a second
+// instruction per element quieting a possible signalling NaN of the freshly loaded value.  With
+// a NaN operand v_med3_f32 returns the smallest non-NaN operand, so a NaN logit simply loses;
+// it still poisons the sum of exponentials, which is what flags the row.  `pinf` is +inf handed
+// in as a kernel argument, so that it lives in a scalar register and the compiler cannot turn
+// the median back into the two-instruction maximum.
+__device__ __forceinline__ float jot_max_raw(float a, float b, float pinf)
+{
+    return __builtin_amdgcn_fmed3f(a, b, pinf);
+}
+
 // Top-2 of the lane over the N elements of one vector.  The argmax is tracked per VECTOR: if
 // some element is strictly larger than the lane maximum so far, remember the vector (index and
 // raw bits); which element it was is found once, after the loop.  Strict comparison keeps the
 // first of equal maxima, because a lane meets its vectors in ascending index order.
 template <int N>
-__device__ __forceinline__ void jot_top2(JotLane& a, const float (&x)[N], const jot_u32x4& raw, int vec_index)
+__device__ __forceinline__ void jot_top2(JotLane& a, const float (&x)[N], const jot_u32x4& raw, int vec_index,
+                                         float pinf)
 {
     const float before = a.m1;
 #pragma unroll
     for (int k = 0; k < N; ++k) {
         a.m2 = __builtin_amdgcn_fmed3f(a.m1, a.m2, x[k]);   // second of {m1, m2, x}
-        a.m1 = fmaxf(a.m1, x[k]);
+        a.m1 = jot_max_raw(a.m1, x[k], pinf);
     }
     const bool better = a.m1 > before;
     a.best_vec = better ? vec_index : a.best_vec;
@@ -86,7 +114,8 @@ __device__ __forceinline__ void jot_expsum(JotLane& a, const float (&x)[N])
 struct JotF32 {
     static constexpr int VEC = 4;              // elements per 16-byte vector
     static constexpr int ESZ = 4;
-    static constexpr int UNROLL = 8;           // vectors in flight per thread
+    static constexpr int UNROLL = JOT_F32_UNROLL;   // vectors in flight per thread
+    static constexpr int WG = JOT_F32_WG;           // threads per workgroup
     static constexpr uint32_t NEG_INF_WORD = 0xff800000u;   // one -inf
     __device__ static __forceinline__ void unpack(const jot_u32x4& w, float (&x)[VEC])
     {
@@ -102,7 +131,8 @@ struct JotF32 {
 struct JotBF16 {
     static constexpr int VEC = 8;
     static constexpr int ESZ = 2;
-    static constexpr int UNROLL = 4;
+    static constexpr int UNROLL = JOT_BF16_UNROLL;
+    static constexpr int WG = JOT_BF16_WG;
     static constexpr uint32_t NEG_INF_WORD = 0xff80ff80u;   // two -inf
     // a bf16 is the upper half of a binary32: widening is a shift / mask, exact
     __device__ static __forceinline__ void unpack(const jot_u32x4& w, float (&x)[VEC])
@@ -119,20 +149,22 @@ struct JotBF16 {
 };
 
 template <class T>
-__global__ __launch_bounds__(JOT_WG) void jot_vocab_reduce_kernel(
+__global__ __launch_bounds__(T::WG) void jot_vocab_reduce_kernel(
     const void* __restrict__ logits, int64_t stride_b, int64_t stride_l, int L, int V,
     const int32_t* __restrict__ active, const JotCounters* __restrict__ counters,
-    JotPartial* __restrict__ partials, int target_items)
+    JotPartial* __restrict__ partials, int target_items, float pos_inf)
 {
     constexpr int VEC = T::VEC;
     constexpr int U = T::UNROLL;
+    constexpr int WG = T::WG;
+    constexpr int WAVES = WG / 64;
     const int64_t n_active = counters->n_active;
-    const JotSplit sp = jot_plan_split(n_active, V, target_items);
+    const JotSplit sp = jot_plan_split(n_active, V, target_items, WG * VEC * U);
     const int64_t n_items = n_active * sp.S;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    __shared__ JotPartial wave_part[JOT_WAVES];
+    __shared__ JotPartial wave_part[WAVES];
 
     for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
         const int64_t r = item / sp.S;
@@ -142,7 +174,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_vocab_reduce_kernel(
         const int i = pos - b * L;
         const char* row = reinterpret_cast<const char*>(logits) +
                           ((int64_t)b * stride_b + (int64_t)i * stride_l) * T::ESZ;
-        const int v0 = piece * sp.chunk;                       // multiple of JOT_CHUNK_ALIGN
+        const int v0 = piece * sp.chunk;                       // whole batches: keeps 16-byte alignment
         const int v1 = min(V, v0 + sp.chunk);
         const int nvec = (v1 - v0) / VEC;                      // whole 16-byte vectors
         const jot_u32x4* __restrict__ p =
@@ -153,17 +185,17 @@ __global__ __launch_bounds__(JOT_WG) void jot_vocab_reduce_kernel(
 
         // Whole batches of U vectors per thread, all loads of a batch issued before any is used.
         int base = 0;                                          // workgroup-uniform
-        for (; base + U * JOT_WG <= nvec; base += U * JOT_WG) {
+        for (; base + U * WG <= nvec; base += U * WG) {
             const int c = base + tid;
             jot_u32x4 w[U];
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                w[u] = __builtin_nontemporal_load(p + c + u * JOT_WG);
+                w[u] = __builtin_nontemporal_load(p + c + u * WG);
             float x[U][VEC];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 T::unpack(w[u], x[u]);
-                jot_top2<VEC>(a, x[u], w[u], c + u * JOT_WG);
+                jot_top2<VEC>(a, x[u], w[u], c + u * WG, pos_inf);
             }
             jot_rereference(a);
 #pragma unroll
@@ -177,7 +209,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_vocab_reduce_kernel(
             jot_u32x4 w[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int cu = c + u * JOT_WG;
+                const int cu = c + u * WG;
                 const bool in = cu < nvec;
                 const jot_u32x4 got = __builtin_nontemporal_load(p + (in ? cu : 0));
                 w[u].x = in ? got.x : T::NEG_INF_WORD;
@@ -189,7 +221,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_vocab_reduce_kernel(
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 T::unpack(w[u], x[u]);
-                jot_top2<VEC>(a, x[u], w[u], c + u * JOT_WG);
+                jot_top2<VEC>(a, x[u], w[u], c + u * WG, pos_inf);
             }
             jot_rereference(a);
 #pragma unroll
@@ -214,7 +246,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_vocab_reduce_kernel(
                 const float xs = T::scalar(row, v);
                 a.m2 = __builtin_amdgcn_fmed3f(a.m1, a.m2, xs);
                 idx = (xs > a.m1) ? v : idx;
-                a.m1 = fmaxf(a.m1, xs);
+                a.m1 = jot_max_raw(a.m1, xs, pos_inf);
                 jot_rereference(a);
                 const float xa[1] = { xs };
                 jot_expsum<1>(a, xa);
@@ -244,7 +276,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_vocab_reduce_kernel(
         if (tid == 0) {
             JotPartial q = wave_part[0];
 #pragma unroll
-            for (int k = 1; k < JOT_WAVES; ++k) {
+            for (int k = 1; k < WAVES; ++k) {
                 const JotPartial o = wave_part[k];
                 jot_merge(q.m1, q.idx, q.m2, q.M, q.s, o.m1, o.idx, o.m2, o.M, o.s);
             }
