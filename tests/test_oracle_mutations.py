@@ -1,0 +1,174 @@
+"""Do the pins bite?  Each case plants one plausible mistake IN THE ORACLE (on the CPU, in a
+copy that is thrown away) and checks that at least one pin of tests/test_oracle_pins.py fails.
+"""
+import ctypes
+import json
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+import test_oracle_pins as P
+from oracle import jot_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+PRINTED = json.load(open(os.path.join(ROOT, "tests", "golden", "paper_printed_values.json")))
+
+
+def pin_battery():
+    """A representative battery of pins as (name, thunk)."""
+    b = [
+        ("sum_to_one", lambda: [P.test_probabilities_sum_to_one_and_match_scipy(V) for V in (2, 16, 257)]),
+        ("uniform", P.test_uniform_row),
+        ("shift_inf", P.test_shift_invariance_and_minus_inf_is_deletion),
+        ("bf16", P.test_bf16_is_widened_exactly),
+        ("ratio_printed", lambda: P.test_ratio_closed_form_and_printed_logit_gaps(PRINTED)),
+        ("top2_brute", lambda: [P.test_top2_and_argmax_brute_force_small_vocab(s) for s in range(20)]),
+        ("dup_max", P.test_duplicated_maximum_gives_ratio_one_and_lowest_index),
+        ("perm", P.test_vocabulary_permutation),
+        ("wmax", lambda: P.test_w_max_closed_forms(PRINTED)),
+        ("eq3_loop", lambda: [P.test_spatial_weight_against_double_loop(g, D) for g, D in ((0.5, 8), (0.9, 16), (1.0, 3))]),
+        ("tau_special", lambda: P.test_threshold_special_cases(PRINTED)),
+        ("all_masks", lambda: [P.test_every_mask_matches_brute_force(*a) for a in (
+            (8, 16, O.CONF_RATIO, 7.0, 0.8, 0), (8, 5, O.CONF_MAXPROB, 0.6, 0.0, 0),
+            (7, 16, O.CONF_PROBGAP, 0.5, 0.05, 0), (8, 9, O.CONF_RATIO, 3.0, 0.8, 3))]),
+        ("tau_zero", lambda: [P.test_threshold_zero_finalizes_everything_in_one_step(m) for m in (0, 1, 2)]),
+        ("tau_above_one", lambda: [P.test_threshold_above_one_finalizes_nothing(m) for m in (1, 2)]),
+        ("invariants", lambda: [P.test_loop_invariants(b, O.CONF_RATIO, 20.0, 1.0) for b in (0, 4)]),
+        ("monotone", P.test_monotonicity_in_tau_max_and_spatial_only_helps),
+        ("simultaneous", P.test_simultaneous_update_within_a_step),
+    ]
+    return b
+
+
+def failing_pins():
+    failed = []
+    for name, thunk in pin_battery():
+        try:
+            thunk()
+        except Exception:
+            failed.append(name)
+    return failed
+
+
+def test_battery_is_green_without_mutation():
+    assert failing_pins() == []
+
+
+# ---- mistakes in the numpy part ------------------------------------------------------------
+
+def _sw_one_sided(resolved, gamma, D):
+    B, L = resolved.shape
+    res = resolved.astype(np.float64)
+    w = np.zeros((B, L))
+    for d in range(1, D + 1):
+        if d < L:
+            w[:, d:] += gamma ** d * res[:, :-d]
+    return w
+
+
+def _sw_short_window(resolved, gamma, D):
+    return O.__dict__["_orig_spatial_weight"](resolved, gamma, max(D - 1, 0))
+
+
+def _sw_wrong_power(resolved, gamma, D):
+    B, L = resolved.shape
+    res = resolved.astype(np.float64)
+    w = np.zeros((B, L))
+    for d in range(1, D + 1):
+        if d < L:
+            w[:, d:] += gamma ** (d - 1) * res[:, :-d]
+            w[:, :-d] += gamma ** (d - 1) * res[:, d:]
+    return w
+
+
+def _thr_wrong_sign(resolved, p):
+    phi = np.minimum(1.0, O.spatial_weight(resolved, p.gamma, p.D) / O.w_max(p.gamma, p.D)) if p.D else np.zeros(resolved.shape)
+    return p.tau_max + (p.tau_max - p.tau_min) * phi, phi
+
+
+def _conf_no_eps(p1, p2, mode, eps):
+    return O.__dict__["_orig_confidence"](p1, p2, mode, 0.0 if mode == O.CONF_RATIO else eps)
+
+
+def _conf_inverted(p1, p2, mode, eps):
+    if mode == O.CONF_RATIO:
+        return p2 / (p1 + eps)
+    if mode == O.CONF_PROBGAP:
+        return p1 + p2
+    return p2
+
+
+def _eligible_ignores_blocks(masked, p):
+    return masked.copy()
+
+
+PY_MUTATIONS = {
+    "one_sided_window": ("spatial_weight", _sw_one_sided),
+    "window_off_by_one": ("spatial_weight", _sw_short_window),
+    "kernel_power_off_by_one": ("spatial_weight", _sw_wrong_power),
+    "w_max_without_factor_two": ("w_max", lambda g, D: sum(g ** d for d in range(1, D + 1))),
+    "threshold_sign": ("threshold", _thr_wrong_sign),
+    "ratio_without_eps": ("confidence", _conf_no_eps),
+    "confidence_inverted": ("confidence", _conf_inverted),
+    "block_restriction_dropped": ("eligible", _eligible_ignores_blocks),
+}
+
+
+@pytest.mark.parametrize("name", sorted(PY_MUTATIONS))
+def test_python_level_mistake_is_caught(name, monkeypatch):
+    attr, repl = PY_MUTATIONS[name]
+    monkeypatch.setitem(O.__dict__, "_orig_" + attr, getattr(O, attr))
+    monkeypatch.setattr(O, attr, repl)
+    assert failing_pins(), f"no pin notices: {name}"
+
+
+def test_sequential_update_is_caught(monkeypatch):
+    orig = O.OracleState.evaluate
+
+    def evaluate_sequential(self, rows):
+        # decide positions one at a time, each seeing the commits made before it in the same step
+        rec = orig(self, rows)
+        masked = self.masked.copy()
+        flat = masked.reshape(-1)
+        for k in range(rec.active.size):
+            tau_all, phi_all = O.threshold(~masked, self.params)
+            rec.tau[k] = tau_all.reshape(-1)[rec.active[k]]
+            rec.commit[k] = rec.status[k] == 0 and rec.conf[k] >= rec.tau[k]
+            if rec.commit[k]:
+                flat[rec.active[k]] = False
+        return rec
+
+    monkeypatch.setattr(O.OracleState, "evaluate", evaluate_sequential)
+    assert failing_pins()
+
+
+# ---- mistakes in the C part ---------------------------------------------------------------
+
+C_MUTATIONS = {
+    "last_index_on_ties": (r"if \(x > best\) \{", "if (x >= best) {"),
+    "second_max_includes_the_winner": (r"if \(v == arg\)\s*\n\s*continue;", ""),
+    "no_max_subtraction": (r"sum \+= exp\(widen\(row, dtype, v\) - best\);", "sum += exp(widen(row, dtype, v));"),
+    "sum_skips_last_entry": (r"for \(int32_t v = 0; v < V; v\+\+\)\n        sum \+=", "for (int32_t v = 0; v < V - 1; v++)\n        sum +="),
+    "bf16_shift": (r"<< 16;", "<< 15;"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(C_MUTATIONS))
+def test_c_level_mistake_is_caught(name, monkeypatch, tmp_path):
+    pat, repl = C_MUTATIONS[name]
+    src = open(os.path.join(ROOT, "oracle", "jot_oracle.c")).read()
+    mutated, n = re.subn(pat, repl, src)
+    assert n >= 1, "mutation pattern no longer matches the oracle source"
+    cfile, lib = tmp_path / "mut.c", tmp_path / "libmut.so"
+    cfile.write_text(mutated)
+    subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", str(lib), str(cfile), "-lm"])
+    good = O._load()
+    mut = ctypes.CDLL(str(lib))
+    for fn in ("jot_oracle_row_stats", "jot_oracle_softmax_row"):
+        getattr(mut, fn).argtypes = getattr(good, fn).argtypes
+        getattr(mut, fn).restype = getattr(good, fn).restype
+    monkeypatch.setattr(O, "_lib", mut)
+    assert failing_pins(), f"no pin notices: {name}"
