@@ -25,6 +25,16 @@ the canvas contribute nothing to Eq. 3; d = 0 is excluded (i itself is masked);
 D = 0 means no spatial modulation (phi = 0); a row with NaN / +inf logits, or
 only -inf logits, is never finalized.
 
+Transfer schedule (Section 3.2 "Iterative Sampling"; Section 4.2 "Interaction with transfer
+schedules" and "Implementation details"): each step the decoder's own schedule reveals a number
+k of the masked positions, those with the highest confidence max_v pi_v; the early-exit mask is
+OR-ed on top of it and is uncapped.  Here: per batch row b, among the positions examined this
+step, U_b = the k_b positions with the largest p1 (equal p1: lower index first), and the step
+finalizes J_b | U_b where J_b is the set passing Eq. 6.  k_b = min(valid_b, n_transfer[b] +
+floor(transfer_frac * examined_b)): an absolute count per row (a precomputed per-step table, as
+in block-wise decoders) plus a fraction of what is still examined (as in decoders that reveal
+num_masked * (1 - s/t) per step).  Rows without a softmax are never selected.
+
 Besides the paper's ratio r, two other confidence signals computed from the same
 (p1, p2) are selectable, because the workloads this is tested on quote
 thresholds on the probability scale: p1 itself, and the gap p1 - p2.
@@ -192,8 +202,11 @@ class StepRecord:
     conf: np.ndarray            # [A]
     tau: np.ndarray             # [A] tau^i
     phi: np.ndarray             # [A]
-    commit: np.ndarray          # [A] bool
+    commit: np.ndarray          # [A] bool: finalized this step (early exit OR schedule)
     status: np.ndarray          # [A] 1 = row without a softmax (never committed)
+    exit: np.ndarray = None     # [A] bool: passed Eq. 6
+    sched: np.ndarray = None    # [A] bool: picked by the transfer schedule
+    k_row: np.ndarray = None    # [B] number of positions the schedule picked per batch row
 
 
 @dataclass
@@ -222,9 +235,10 @@ class OracleState:
     def active_count(self) -> int:
         return int(self.active_list().size)
 
-    def evaluate(self, rows: np.ndarray) -> StepRecord:
+    def evaluate(self, rows: np.ndarray, n_transfer=None, transfer_frac: float = 0.0) -> StepRecord:
         """Decisions of the next step for the given logit rows (rows[k] belongs to
-        active_list()[k]) WITHOUT changing the state."""
+        active_list()[k]) WITHOUT changing the state.  n_transfer ([B] ints) and transfer_frac
+        describe the transfer schedule of this step; by default it reveals nothing."""
         p = self.params
         act = self.active_list()
         if rows.shape[0] != act.size:
@@ -240,8 +254,31 @@ class OracleState:
         tau = tau_all.reshape(-1)[act]
         phi = phi_all.reshape(-1)[act]
         with np.errstate(invalid="ignore"):
-            commit = ok & (conf >= tau)                         # Eq. 6
-        return StepRecord(self.step_index + 1, act, a, p1, p2, conf, tau, phi, commit, st)
+            exit_ = ok & (conf >= tau)                          # Eq. 6
+        sched, k_row = self._schedule(act, p1, ok, n_transfer, transfer_frac)
+        commit = exit_ | sched                                  # logical OR, uncapped
+        return StepRecord(self.step_index + 1, act, a, p1, p2, conf, tau, phi, commit, st,
+                          exit_, sched, k_row)
+
+    def _schedule(self, act, p1, ok, n_transfer, transfer_frac):
+        """Per batch row: the k positions with the largest p1 among the examined ones."""
+        p = self.params
+        sched = np.zeros(act.size, bool)
+        k_row = np.zeros(p.B, np.int64)
+        if n_transfer is None and transfer_frac == 0.0:
+            return sched, k_row
+        n_transfer = np.zeros(p.B, np.int64) if n_transfer is None else np.asarray(n_transfer, np.int64)
+        row_of = act // p.L
+        for b in range(p.B):
+            mine = np.flatnonzero(row_of == b)                  # ascending position
+            valid = mine[ok[mine]]
+            k = int(n_transfer[b]) + int(np.floor(float(transfer_frac) * mine.size))
+            k = max(0, min(k, valid.size))
+            k_row[b] = k
+            if k:
+                order = sorted(valid.tolist(), key=lambda j: (-p1[j], j))   # largest p1, then lowest index
+                sched[order[:k]] = True
+        return sched, k_row
 
     def apply(self, rec: StepRecord) -> None:
         """Commit the step: all finalizations take effect together."""
@@ -257,14 +294,14 @@ class OracleState:
             self.commit_log.append((rec.step, pos, int(rec.token[k])))
         self.anomalies += int(rec.status.sum())
 
-    def step(self, rows: np.ndarray) -> StepRecord:
-        rec = self.evaluate(rows)
+    def step(self, rows: np.ndarray, n_transfer=None, transfer_frac: float = 0.0) -> StepRecord:
+        rec = self.evaluate(rows, n_transfer, transfer_frac)
         self.apply(rec)
         return rec
 
-    def step_full(self, logits: np.ndarray) -> StepRecord:
+    def step_full(self, logits: np.ndarray, n_transfer=None, transfer_frac: float = 0.0) -> StepRecord:
         """Convenience for small cases: logits is the whole [B, L, V] array."""
         p = self.params
         act = self.active_list()
         rows = logits.reshape(p.B * p.L, p.V)[act]
-        return self.step(rows)
+        return self.step(rows, n_transfer, transfer_frac)

@@ -11,6 +11,7 @@ import numpy as np
 import pytest
 
 import test_oracle_pins as P
+import test_oracle_schedule_pins as S
 from oracle import jot_oracle as O
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -39,6 +40,14 @@ def pin_battery():
         ("invariants", lambda: [P.test_loop_invariants(b, O.CONF_RATIO, 20.0, 1.0) for b in (0, 4)]),
         ("monotone", P.test_monotonicity_in_tau_max_and_spatial_only_helps),
         ("simultaneous", P.test_simultaneous_update_within_a_step),
+        ("sched_all_masks", lambda: [S.test_every_mask_matches_brute_force_with_schedule(*a) for a in (
+            (7, 8, O.CONF_RATIO, 9.0, 0.8, 0, 1, 0.0), (6, 5, O.CONF_RATIO, 50.0, 0.8, 0, 0, 0.5),
+            (8, 6, O.CONF_PROBGAP, 0.6, 0.05, 3, 1, 0.34))]),
+        ("sched_default", S.test_no_schedule_is_the_default_and_k_zero_changes_nothing),
+        ("sched_plain_topk", S.test_unreachable_threshold_degrades_to_plain_top_k_decoding),
+        ("sched_fraction", S.test_fraction_one_reveals_everything_and_fraction_is_floored),
+        ("sched_ties", S.test_equal_confidence_is_ranked_by_position_and_rows_without_softmax_are_skipped),
+        ("sched_blocks", S.test_schedule_stays_inside_the_current_block_and_guarantees_termination),
     ]
     return b
 
@@ -128,9 +137,9 @@ def test_python_level_mistake_is_caught(name, monkeypatch):
 def test_sequential_update_is_caught(monkeypatch):
     orig = O.OracleState.evaluate
 
-    def evaluate_sequential(self, rows):
+    def evaluate_sequential(self, rows, n_transfer=None, transfer_frac=0.0):
         # decide positions one at a time, each seeing the commits made before it in the same step
-        rec = orig(self, rows)
+        rec = orig(self, rows, n_transfer, transfer_frac)
         masked = self.masked.copy()
         flat = masked.reshape(-1)
         for k in range(rec.active.size):
@@ -142,6 +151,59 @@ def test_sequential_update_is_caught(monkeypatch):
         return rec
 
     monkeypatch.setattr(O.OracleState, "evaluate", evaluate_sequential)
+    assert failing_pins()
+
+
+def _sched_variant(kind):
+    def _schedule(self, act, p1, ok, n_transfer, transfer_frac):
+        p = self.params
+        sched = np.zeros(act.size, bool)
+        k_row = np.zeros(p.B, np.int64)
+        if n_transfer is None and transfer_frac == 0.0:
+            return sched, k_row
+        n_transfer = np.zeros(p.B, np.int64) if n_transfer is None else np.asarray(n_transfer, np.int64)
+        row_of = act // p.L
+        if kind == "global_top_k":
+            valid = np.flatnonzero(ok)
+            k = int(n_transfer.sum()) + int(np.floor(transfer_frac * act.size))
+            order = sorted(valid.tolist(), key=lambda j: (-p1[j], j))
+            sched[order[:k]] = True
+            return sched, k_row
+        for b in range(p.B):
+            mine = np.flatnonzero(row_of == b)
+            valid = mine if kind == "selects_rows_without_softmax" else mine[ok[mine]]
+            x = float(transfer_frac) * mine.size
+            k = int(n_transfer[b]) + int(np.ceil(x) if kind == "fraction_rounded_up" else np.floor(x))
+            k = max(0, min(k, valid.size))
+            k_row[b] = k
+            if kind == "least_confident_first":
+                key = lambda j: (p1[j], j)
+            elif kind == "ties_to_higher_index":
+                key = lambda j: (-p1[j], -j)
+            else:
+                key = lambda j: (-np.nan_to_num(p1[j], nan=2.0), j)
+            sched[sorted(valid.tolist(), key=key)[:k]] = True
+        return sched, k_row
+    return _schedule
+
+
+@pytest.mark.parametrize("kind", ["least_confident_first", "ties_to_higher_index", "global_top_k",
+                                  "fraction_rounded_up", "selects_rows_without_softmax"])
+def test_schedule_mistake_is_caught(kind, monkeypatch):
+    monkeypatch.setattr(O.OracleState, "_schedule", _sched_variant(kind))
+    assert failing_pins(), f"no pin notices: {kind}"
+
+
+def test_and_instead_of_or_is_caught(monkeypatch):
+    orig = O.OracleState.evaluate
+
+    def evaluate_and(self, rows, n_transfer=None, transfer_frac=0.0):
+        rec = orig(self, rows, n_transfer, transfer_frac)
+        if n_transfer is not None or transfer_frac:
+            rec.commit = rec.exit & rec.sched
+        return rec
+
+    monkeypatch.setattr(O.OracleState, "evaluate", evaluate_and)
     assert failing_pins()
 
 
