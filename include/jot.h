@@ -111,6 +111,24 @@ int jot_init_state(jot_state** out, const jot_params* p,
  */
 int jot_step(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l, void* stream);
 
+/*
+ * jot_step plus the decoder's transfer schedule (Section 3.2 "Iterative Sampling"; Section 4.2
+ * "Interaction with transfer schedules", "Implementation details": the schedule reveals the k
+ * most confident masked positions, confidence = max_v pi_v, and the early-exit mask is OR-ed on
+ * top of it, uncapped).  Per batch row b, of the positions examined this step the
+ *     k_b = min(#rows with a softmax, n_transfer[b] + floor(transfer_frac * #examined in row b))
+ * with the largest p1 (equal p1: lower position first) are finalized with their argmax token, in
+ * addition to every position that passes Eq. 6.  In block mode the schedule, like the early
+ * exit, acts inside the row's current block.
+ *   n_transfer_dev : [B] int32 DEVICE array (a per-step entry of a precomputed schedule), or NULL
+ *                    for all zeros; negative totals count as 0
+ *   transfer_frac  : in [0, 1]; e.g. 1 - s/t for decoders that reveal num_masked * (1 - s/t),
+ *                    1.0 on the last step reveals everything that has a softmax
+ * jot_step(...) is jot_step_scheduled(..., NULL, 0.0f, ...).  Same asynchrony and errors.
+ */
+int jot_step_scheduled(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
+                       const int32_t* n_transfer_dev, float transfer_frac, void* stream);
+
 /* Number of positions the NEXT step would examine (0 = decoding finished).  Waits for the work
  * enqueued so far on this state.  <0: JOT_ERR_*. */
 int64_t jot_active_count(jot_state* s);
@@ -144,6 +162,8 @@ const float*   jot_last_conf(const jot_state* s);
 const float*   jot_last_p1(const jot_state* s);
 const float*   jot_last_p2(const jot_state* s);
 const float*   jot_last_tau(const jot_state* s);
+/* per examined position: bit 0 = passed Eq. 6, bit 1 = picked by the transfer schedule */
+const uint8_t* jot_last_flags(const jot_state* s);
 
 /*
  * Optional timing of the vocabulary-reduction kernel (the one that reads the logits):

@@ -12,6 +12,7 @@
 #include "jot_compact.h"
 #include "jot_decide.h"
 #include "jot_device.h"
+#include "jot_schedule.h"
 #include "jot_vocab_reduce.h"
 
 namespace {
@@ -29,7 +30,7 @@ constexpr int kItemsPerWg = 4;
 
 struct Layout {
     int64_t tokens, masked, commit_step, resolved_bits, active0, active1, counters, anomalies,
-        partials, last_token, last_conf, last_p1, last_p2, last_tau, row_block, row_n_active,
+        partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, row_block, row_n_active,
         row_n_commit, commit_log, total;
     int64_t n_partials;
     int32_t words_per_row;
@@ -76,6 +77,7 @@ Layout make_layout(const jot_params* p, int target_items)
     l.last_p1 = take(n * 4);
     l.last_p2 = take(n * 4);
     l.last_tau = take(n * 4);
+    l.last_flags = take(n);
     l.row_block = take((int64_t)p->B * 4);
     l.row_n_active = take((int64_t)p->B * 4);
     l.row_n_commit = take((int64_t)p->B * 4);
@@ -251,7 +253,15 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
 
 int jot_step(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l, void* stream)
 {
+    return jot_step_scheduled(s, logits_dev, stride_b, stride_l, nullptr, 0.0f, stream);
+}
+
+int jot_step_scheduled(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
+                       const int32_t* n_transfer_dev, float transfer_frac, void* stream)
+{
     if (!s || !logits_dev) return JOT_ERR_NULL_POINTER;
+    if (!(transfer_frac >= 0.0f && transfer_frac <= 1.0f)) return JOT_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(n_transfer_dev) % 4) return JOT_ERR_MISALIGNED;
     const jot_params& p = s->p;
     const int64_t esz = p.dtype == JOT_F32 ? 4 : 2;
     if (stride_l < p.V) return JOT_ERR_INVALID_ARG;
@@ -291,8 +301,18 @@ int jot_step(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t str
                        s->at<int32_t>(s->lay.commit_step), s->at<int32_t>(s->lay.last_token),
                        s->at<float>(s->lay.last_conf), s->at<float>(s->lay.last_p1),
                        s->at<float>(s->lay.last_p2), s->at<float>(s->lay.last_tau),
-                       s->at<unsigned long long>(s->lay.anomalies));
+                       s->at<uint8_t>(s->lay.last_flags), s->at<unsigned long long>(s->lay.anomalies));
     if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
+    if (n_transfer_dev || transfer_frac > 0.0f) {
+        JotScheduleParams sp;
+        sp.B = p.B; sp.L = p.L; sp.transfer_frac = transfer_frac;
+        hipLaunchKernelGGL(jot_schedule_kernel, dim3(p.B), dim3(JOT_WG), 0, st, sp, step, n_transfer_dev,
+                           s->active(in), s->at<int32_t>(s->lay.row_n_active), s->at<float>(s->lay.last_p1),
+                           s->at<float>(s->lay.last_conf), s->at<int32_t>(s->lay.last_token),
+                           s->at<uint8_t>(s->lay.last_flags), s->at<int32_t>(s->lay.tokens),
+                           s->at<int32_t>(s->lay.commit_step));
+        if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
+    }
     s->step = step;
     return enqueue_compaction(s, step, st);
 }
@@ -335,6 +355,7 @@ const float* jot_last_conf(const jot_state* s) { return s ? s->at<float>(s->lay.
 const float* jot_last_p1(const jot_state* s) { return s ? s->at<float>(s->lay.last_p1) : nullptr; }
 const float* jot_last_p2(const jot_state* s) { return s ? s->at<float>(s->lay.last_p2) : nullptr; }
 const float* jot_last_tau(const jot_state* s) { return s ? s->at<float>(s->lay.last_tau) : nullptr; }
+const uint8_t* jot_last_flags(const jot_state* s) { return s ? s->at<uint8_t>(s->lay.last_flags) : nullptr; }
 
 int jot_profile_enable(jot_state* s, int on)
 {

@@ -1,0 +1,126 @@
+// Transfer schedule on top of the early exit (Section 3.2 "Iterative Sampling"; Section 4.2
+// "Interaction with transfer schedules" / "Implementation details": the decoder's schedule
+// reveals the k most confident of the masked positions, confidence = max_v pi_v, and the
+// early-exit mask is OR-ed on top, uncapped).
+//
+// One workgroup per batch row.  Among the positions the row examined this step it selects the
+// k with the largest p1 (equal p1: lower position first) and finalizes those that Eq. 6 has not
+// finalized already.  Selection is exact and order-deterministic: a bitwise radix descent over
+// the binary32 patterns of p1 (positive floats order like unsigned integers) finds the k-th
+// largest value T with wave ballots and popcounts; everything above T is taken, and of the
+// values equal to T the first k - #(> T) in position order, by a ballot prefix scan.
+#pragma once
+#include "jot_device.h"
+
+struct JotScheduleParams {
+    int32_t B, L;
+    float transfer_frac;
+};
+
+__device__ __forceinline__ int jot_wg_sum(int v, int* lds)      // v already summed per wave in lane 0
+{
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    int r = 0;
+#pragma unroll
+    for (int k = 0; k < JOT_WAVES; ++k) r += lds[k];
+    __syncthreads();
+    return r;
+}
+
+__global__ __launch_bounds__(JOT_WG) void jot_schedule_kernel(
+    JotScheduleParams prm, int32_t step, const int32_t* __restrict__ n_transfer,
+    const int32_t* __restrict__ active, const int32_t* __restrict__ row_n_active,
+    const float* __restrict__ last_p1, const float* __restrict__ last_conf,
+    const int32_t* __restrict__ last_token, uint8_t* __restrict__ last_flags,
+    int32_t* __restrict__ tokens, int32_t* __restrict__ commit_step)
+{
+    __shared__ int lds[JOT_WAVES];
+    __shared__ int wave_eq[JOT_WAVES];
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    // this row's slice [base, base + n) of the examined list
+    int pa = 0;
+    for (int k = threadIdx.x; k < b; k += JOT_WG) pa += row_n_active[k];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) pa += __shfl_xor(pa, off, 64);
+    const int64_t base = jot_wg_sum(pa, lds);
+    const int n = row_n_active[b];
+    if (n == 0)
+        return;
+
+    // key of entry j: bit pattern of p1, or 0 for a row without a softmax (conf is NaN there)
+    auto key_of = [&](int j) -> uint32_t {
+        const float c = last_conf[base + j];
+        return (c == c) ? __float_as_uint(last_p1[base + j]) : 0u;
+    };
+
+    // how many to reveal
+    int cv = 0;
+    for (int j0 = 0; j0 < n; j0 += JOT_WG) {
+        const int j = j0 + threadIdx.x;
+        cv += __popcll(__ballot(j < n && key_of(j) != 0u)) * (lane == 0);
+    }
+    const int n_valid = jot_wg_sum(cv, lds);
+    long long want = (n_transfer ? (long long)n_transfer[b] : 0ll) +
+                     (long long)floor((double)prm.transfer_frac * (double)n);
+    if (want > n_valid) want = n_valid;
+    if (want <= 0)
+        return;
+    const int k = (int)want;
+
+    // T = k-th largest key: the largest value with #(key >= T) >= k, built bit by bit
+    uint32_t T = 0u;
+    if (k < n_valid) {
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t cand = T | (1u << bit);
+            int c = 0;
+            for (int j0 = 0; j0 < n; j0 += JOT_WG) {
+                const int j = j0 + threadIdx.x;
+                c += __popcll(__ballot(j < n && key_of(j) >= cand)) * (lane == 0);
+            }
+            if (jot_wg_sum(c, lds) >= k)
+                T = cand;
+        }
+    }                                  // else T = 0: every entry with a softmax (their keys are >= 1)
+    int cg = 0;
+    for (int j0 = 0; j0 < n; j0 += JOT_WG) {
+        const int j = j0 + threadIdx.x;
+        cg += __popcll(__ballot(j < n && key_of(j) > T)) * (lane == 0);
+    }
+    const int n_above = jot_wg_sum(cg, lds);
+    const int need_eq = k - n_above;   // entries equal to T still to take (0 when taking all)
+
+    // take: key > T, and the first need_eq entries with key == T
+    int run_eq = 0;
+    for (int j0 = 0; j0 < n; j0 += JOT_WG) {
+        const int j = j0 + threadIdx.x;
+        const bool in = j < n;
+        const uint32_t key = in ? key_of(j) : 0u;
+        const bool above = in && key > T;
+        const bool equal = in && key != 0u && key == T;
+        const uint64_t m_eq = __ballot(equal);
+        const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+        if (lane == 0) wave_eq[wave] = __popcll(m_eq);
+        __syncthreads();
+        int off = run_eq, tot = 0;
+#pragma unroll
+        for (int w = 0; w < JOT_WAVES; ++w) {
+            if (w < wave) off += wave_eq[w];
+            tot += wave_eq[w];
+        }
+        const bool take = above || (equal && off + __popcll(m_eq & below) < need_eq);
+        if (take) {
+            const int64_t r = base + j;
+            const int pos = active[r];
+            last_flags[r] |= 2;
+            if (commit_step[pos] != step) {          // not already finalized by the early exit
+                tokens[pos] = last_token[r];
+                commit_step[pos] = step;
+            }
+        }
+        run_eq += tot;
+        __syncthreads();
+    }
+}

@@ -43,10 +43,17 @@ class GpuJot:
         except Exception:
             pass
 
-    def step(self, logits: torch.Tensor, stride_b=None, stride_l=None):
+    def step(self, logits: torch.Tensor, stride_b=None, stride_l=None, n_transfer=None, transfer_frac=0.0):
         sb = logits.stride(0) if stride_b is None else stride_b
         sl = logits.stride(1) if stride_l is None else stride_l
-        J.jot_step(self.h, logits.data_ptr(), sb, sl, self.stream)
+        if n_transfer is None and transfer_frac == 0.0:
+            J.jot_step(self.h, logits.data_ptr(), sb, sl, self.stream)
+            return
+        nt = 0
+        if n_transfer is not None:
+            self._nt = torch.from_numpy(np.ascontiguousarray(n_transfer, np.int32)).to(self.dev)
+            nt = self._nt.data_ptr()
+        J.jot_step_scheduled(self.h, logits.data_ptr(), sb, sl, nt, transfer_frac, self.stream)
 
     # ---- read-back
     def active_count(self) -> int:
@@ -78,6 +85,7 @@ class GpuJot:
         out["token"] = J.device_to_host(J.jot_last_token(self.h), n, np.int32)
         for name in ("conf", "p1", "p2", "tau"):
             out[name] = J.device_to_host(getattr(J, "jot_last_" + name)(self.h), n, np.float32)
+        out["flags"] = J.device_to_host(J.jot_last_flags(self.h), n, np.uint8)
         return out
 
 
@@ -120,5 +128,9 @@ def compare_step(gpu_last: dict, rec, act_full: np.ndarray, tol: float, select=N
     big = ok & (rec.p2 > 1e-30)           # p2 below that is subnormal in binary32
     assert rel_err(g["p2"][big], rec.p2[big]).max(initial=0) <= max(tol, 2e-5)
     with np.errstate(invalid="ignore"):
-        commit_gpu = ok & (g["conf"] >= g["tau"])
-    np.testing.assert_array_equal(commit_gpu, rec.commit)
+        exit_gpu = ok & (g["conf"] >= g["tau"])
+    want_exit = rec.exit if rec.exit is not None else rec.commit
+    np.testing.assert_array_equal(exit_gpu, want_exit)
+    np.testing.assert_array_equal((g["flags"] & 1).astype(bool), want_exit)
+    want_sched = rec.sched if rec.sched is not None else np.zeros_like(rec.commit)
+    np.testing.assert_array_equal((g["flags"] & 2).astype(bool), want_sched)

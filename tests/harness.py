@@ -21,11 +21,23 @@ def oracle_params(cfg: JotConfig) -> O.OracleParams:
                           eps=cfg.eps, gen_start=cfg.gen_start, block_size=cfg.block_size)
 
 
-def too_close(rec: O.StepRecord) -> np.ndarray:
+def too_close(rec: O.StepRecord, L: int = 0) -> np.ndarray:
+    """Examined entries whose decision is not well posed: a confidence within the guard band of
+    its threshold, or -- with a transfer schedule -- the last position the schedule takes in a
+    row when the best position it leaves behind has nearly the same p1."""
     ok = rec.status == 0
     with np.errstate(invalid="ignore"):
-        near = np.abs(rec.conf - rec.tau) < GUARD * np.maximum(1.0, np.abs(rec.tau))
-    return np.flatnonzero(ok & near)
+        near = ok & (np.abs(rec.conf - rec.tau) < GUARD * np.maximum(1.0, np.abs(rec.tau)))
+    if rec.sched is not None and rec.sched.any():
+        row_of = rec.active // L
+        for b in np.unique(row_of[rec.sched]):
+            mine = np.flatnonzero((row_of == b) & ok)
+            taken, left = mine[rec.sched[mine]], mine[~rec.sched[mine]]
+            if taken.size and left.size:
+                lo = taken[np.argmin(rec.p1[taken])]
+                if rec.p1[lo] - rec.p1[left].max() < GUARD * rec.p1[lo]:
+                    near[lo] = True
+    return np.flatnonzero(near)
 
 
 class LockstepRun:
@@ -51,18 +63,21 @@ class LockstepRun:
     def active_full(self) -> np.ndarray:
         return self.to_full(self.state.active_list())
 
-    def next_step(self):
+    def next_step(self, n_transfer=None, transfer_frac: float = 0.0):
         """Advance the oracle one step.  Returns (rec, T, R, rows) where rec.active is in
         sub-batch numbering, T/R are the final planted tables of this step (full canvas) and
-        rows are the logit rows the oracle saw (a view valid until the next call)."""
+        rows are the logit rows the oracle saw (a view valid until the next call).
+        n_transfer ([B] of the FULL batch) / transfer_frac: the step's transfer schedule."""
+        if n_transfer is not None:
+            n_transfer = np.asarray(n_transfer)[self.batch_rows]
         st, tr = self.state, self.traj
         n = st.step_index + 1
         act_full = self.active_full()
         T, R = tr.planted(n)
         rows = self.gen.rows(n, act_full, T, R)
-        rec = st.evaluate(rows)
+        rec = st.evaluate(rows, n_transfer, transfer_frac)
         for _ in range(MAX_BUMPS):
-            bad = too_close(rec)
+            bad = too_close(rec, self.cfg.L)
             if bad.size == 0:
                 break
             for k in bad:
@@ -71,7 +86,7 @@ class LockstepRun:
             T, R = tr.planted(n)
             fixer = HostGenerator(self.cfg, tr.target, tr.rival, 1)
             rows[bad] = fixer.rows(n, act_full[bad], T, R)
-            rec = st.evaluate(rows)
+            rec = st.evaluate(rows, n_transfer, transfer_frac)
         else:
             raise RuntimeError("could not clear the guard band")
         st.apply(rec)

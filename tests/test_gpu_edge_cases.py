@@ -10,7 +10,7 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 from gen.bf16 import bf16_bits_to_f32, f32_to_bf16_bits  # noqa: E402
-from harness import GUARD  # noqa: E402
+from harness import GUARD, too_close  # noqa: E402
 from oracle import jot_oracle as O  # noqa: E402
 
 
@@ -27,16 +27,17 @@ def say(msg):
     sys.stdout.flush()
 
 
-def clear_guard_band(st: O.OracleState, logits: np.ndarray):
-    """Adjust the INPUT until no examined position sits within the guard band of its threshold:
-    raise that row's current argmax logit by one."""
+def clear_guard_band(st: O.OracleState, logits: np.ndarray, n_transfer=None, frac=0.0):
+    """Adjust the INPUT until no decision of the step is ill posed (confidence within the guard
+    band of its threshold, or a near-tie at the edge of the schedule's selection): raise that
+    row's current argmax logit by one."""
     p = st.params
     flat = logits.reshape(p.B * p.L, p.V)
     for _ in range(100):
         act = st.active_list()
-        rec = st.evaluate(as_rows(flat[act], p.dtype))
-        with np.errstate(invalid="ignore"):
-            near = (rec.status == 0) & (np.abs(rec.conf - rec.tau) < GUARD * np.maximum(1, np.abs(rec.tau)))
+        rec = st.evaluate(as_rows(flat[act], p.dtype), n_transfer, frac)
+        near = np.zeros(act.size, bool)
+        near[too_close(rec, p.L)] = True
         if not near.any():
             return
         for k in np.flatnonzero(near):
@@ -62,7 +63,9 @@ def to_device(logits: np.ndarray, dtype: int, stride_l: int):
     return dev
 
 
-def check_case(gpu, p: O.OracleParams, tokens, masked, logit_seq, stride_pad=0, tol=None, clear=True):
+def check_case(gpu, p: O.OracleParams, tokens, masked, logit_seq, stride_pad=0, tol=None, clear=True,
+               schedule=None):
+    """schedule: optional list of (n_transfer, frac) per step."""
     import paper_2602_11133_amd as J
     esz = 4 if p.dtype == O.F32 else 2
     align = 16 // esz
@@ -81,14 +84,16 @@ def check_case(gpu, p: O.OracleParams, tokens, masked, logit_seq, stride_pad=0, 
         logits = np.array(logits, np.float32)
         if p.dtype == O.BF16:
             logits = bf16_bits_to_f32(f32_to_bf16_bits(logits)).reshape(logits.shape)
+        nt, frac = schedule[n - 1] if schedule else (None, 0.0)
+        frac = float(np.float32(frac))
         if clear:
-            clear_guard_band(st, logits)
+            clear_guard_band(st, logits, nt, frac)
             if p.dtype == O.BF16:
                 assert np.array_equal(bf16_bits_to_f32(f32_to_bf16_bits(logits)).reshape(logits.shape), logits)
         act = st.active_list()
-        rec = st.step(as_rows(logits.reshape(p.B * p.L, p.V)[act], p.dtype))
+        rec = st.step(as_rows(logits.reshape(p.B * p.L, p.V)[act], p.dtype), nt, frac)
         dev = to_device(logits, p.dtype, stride_l)
-        g.step(dev, stride_b=p.L * stride_l, stride_l=stride_l)
+        g.step(dev, stride_b=p.L * stride_l, stride_l=stride_l, n_transfer=nt, transfer_frac=frac)
         gpu.compare_step(g.last(), rec, act, tol)
         np.testing.assert_array_equal(g.tokens(), st.tokens)
         np.testing.assert_array_equal(g.masked(), st.masked)
@@ -243,4 +248,49 @@ def test_two_runs_are_bitwise_identical(gpu):
     for x, y in zip(a[:3], b[:3]):
         np.testing.assert_array_equal(x, y)
     for k in a[3]:
-        np.testing.assert_array_equal(a[3][k].view(np.uint32), b[3][k].view(np.uint32))
+        np.testing.assert_array_equal(a[3][k].view(np.uint8), b[3][k].view(np.uint8))
+
+
+# --------------------------------------------------------------------------- transfer schedule
+
+@pytest.mark.parametrize("mode,tau_max,tau_min", [(O.CONF_RATIO, 90.0, 1.0), (O.CONF_MAXPROB, 0.9, 0.0),
+                                                   (O.CONF_RATIO, 1e9, 1e9)])
+def test_schedule_counts_and_fractions(gpu, mode, tau_max, tau_min):
+    say(f"[edge] schedule mode={mode} tau_max={tau_max}")
+    p, tokens, masked, seq = random_case(41 + mode, B=5, L=150, V=300, gs=20, conf_mode=mode, tau_max=tau_max,
+                                         tau_min=tau_min, gamma=0.5, D=8, steps=7)
+    sched = [([1, 0, 3, 200, 7], 0.0), (None, 0.25), ([0, 0, 0, 0, 0], 0.0), ([2, 2, 2, 2, 2], 0.1),
+             ([1, 1, 1, 1, 1], 0.0), (None, 0.5), (None, 1.0)]
+    toks, msk, log, last = check_case(gpu, p, tokens, masked, seq, schedule=sched)
+    assert not msk.any()                      # the last step (fraction 1) reveals everything
+
+
+def test_schedule_in_block_mode(gpu):
+    p, tokens, masked, seq = random_case(43, B=3, L=100, V=200, gs=12, conf_mode=O.CONF_RATIO, tau_max=30.0,
+                                         tau_min=1.0, gamma=0.5, D=8, block_size=16, steps=12)
+    check_case(gpu, p, tokens, masked, seq, schedule=[([2, 1, 3], 0.0)] * 12)
+
+
+def test_schedule_with_equal_confidences_and_rows_without_softmax(gpu):
+    B, L, V = 2, 300, 64
+    p = O.OracleParams(B=B, L=L, V=V, dtype=O.F32, conf_mode=O.CONF_MAXPROB, tau_max=2.0, tau_min=1.5, D=0)
+    lg = np.zeros((B, L, V), np.float32)
+    lg[:, :, 5] = 4.0                          # identical rows: every p1 is the same bit pattern
+    lg[0, 7, 9] = np.nan
+    lg[0, 8, :] = -np.inf
+    lg[1, 100:110, 6] = 6.0                    # ten rows with a larger p1 ...
+    lg[1, 200:205, 5] = 9.0                    # ... and five with a still larger one
+    masked = np.ones((B, L), bool)
+    sched = [([3, 7], 0.0), ([290, 0], 0.0), ([1000, 1000], 0.0)]
+    toks, msk, log, last = check_case(gpu, p, np.zeros((B, L), np.int32), masked, [lg, lg, lg], clear=False,
+                                      schedule=sched)
+    assert log[:3, 1].tolist() == [0, 1, 2]                       # equal confidence: lowest positions first
+    assert sorted(log[3:10, 1].tolist()) == [L + 100, L + 101, L + 200, L + 201, L + 202, L + 203, L + 204]
+    assert msk[0, 7] and msk[0, 8] and msk.sum() == 2             # rows without a softmax are never revealed
+
+
+def test_schedule_on_a_long_row(gpu):
+    # several 256-wide chunks per row in the selection kernel, L not a multiple of anything
+    p, tokens, masked, seq = random_case(47, B=2, L=2500, V=48, gs=3, conf_mode=O.CONF_MAXPROB, tau_max=0.95,
+                                         tau_min=0.0, gamma=0.5, D=8, steps=3)
+    check_case(gpu, p, tokens, masked, seq, schedule=[([1, 1999], 0.0), (None, 0.37), ([5, 5], 0.5)])

@@ -34,7 +34,7 @@ def gpu():
     return gpu_harness
 
 
-def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True):
+def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True, schedule=None):
     """Lock-step decode: oracle on the host (optionally on a subset of batch rows), library on
     the GPU over the whole batch; compares every step and the final state."""
     from gen.device import DeviceGenerator
@@ -54,14 +54,16 @@ def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True):
         if run.state.active_count() == 0:
             break
         act_full = run.active_full()
-        rec, T, R, rows = run.next_step()
+        nt, frac = schedule(n) if schedule else (None, 0.0)
+        frac = float(np.float32(frac))
+        rec, T, R, rows = run.next_step(nt, frac)
         n_gpu = g.active_count()
         if use_device_gen:
             dgen.set_planted(T, R)
             dgen.fill(logits, n, J.jot_active_list(g.h), n_gpu)
         else:
             gpu.upload_rows(logits, act_full, rows, cfg.dtype)
-        g.step(logits)
+        g.step(logits, n_transfer=nt, transfer_frac=frac)
         last = g.last()
         sel = followed[last["active"] // cfg.L] if batch_rows is not None else None
         gpu.compare_step(last, rec, act_full, TOL[cfg.dtype], sel)
@@ -172,3 +174,25 @@ def test_config5_probgap_short(gpu):
     cfg = CONFIGS[5].replace(conf_mode=CONF_PROBGAP, tau_max=0.9, tau_min=0.0, B=2, L=256 + 128,
                              steps=32, base="partition", noise_scale=0.02)
     run_parity(gpu, cfg)
+
+
+# --------------------------------------------------------------------------- with a transfer schedule
+
+def test_config2_with_fractional_schedule(gpu):
+    # a decoder that reveals remaining/steps_left positions per step (so it ends on the last
+    # configured step at the latest), with the early exit on top
+    cfg = CONFIGS[2].replace(steps=48, L=64 + 192)
+    n = run_parity(gpu, cfg, schedule=lambda n: (None, 1.0 / max(1, cfg.steps - n + 1)))
+    assert n <= cfg.steps
+
+
+def test_config4_with_one_token_per_step_schedule(gpu):
+    # block-wise decoder: one position per row per step from the schedule, early exit on top
+    cfg = CONFIGS[4].replace(B=8, L=128 + 128, steps=128)
+    n = run_parity(gpu, cfg, batch_rows=[0, 3, 7], schedule=lambda n: (np.ones(cfg.B, np.int32), 0.0))
+    assert n <= cfg.n_gen
+
+
+def test_config5_ratio_with_schedule_short(gpu):
+    cfg = CONFIGS[5].replace(B=4, steps=24)
+    run_parity(gpu, cfg, batch_rows=[1, 2], max_steps=24, schedule=lambda n: (np.full(cfg.B, 8, np.int32), 0.02))
