@@ -135,6 +135,9 @@ def main():
     ap.add_argument("--cpu-sample-rows", type=int, default=16, help="batch rows timed on the CPU oracle")
     ap.add_argument("--dtype", choices=["f32", "bf16"], default=None,
                     help="override the logit type of the workload (changes the workload: for tuning)")
+    ap.add_argument("--schedule", choices=["none", "linear"], default="none",
+                    help="also apply a transfer schedule each step: 'linear' reveals "
+                         "remaining/steps_left of every row's examined positions (jot_step_scheduled)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
@@ -196,7 +199,11 @@ def main():
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for k in range(seg):
-                J.jot_step(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, stream)
+                if args.schedule == "linear":
+                    frac = 1.0 / max(1, cfg.steps - (done + k + 1) + 1)
+                    J.jot_step_scheduled(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, 0, frac, stream)
+                else:
+                    J.jot_step(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, stream)
                 a_next = J.jot_active_count(g.h)        # the decode loop's termination test
                 examined.append(a_prev)
                 a_prev = a_next
@@ -233,13 +240,13 @@ def main():
         "config": {"workload": f"{cfg.name}: B={cfg.B}, L={cfg.L} ({cfg.gen_start} prompt + {cfg.n_gen} generated), "
                                f"V={cfg.V}, decode steps 1..{K}", "examined_positions_per_step": examined,
                    "conf_mode": cfg.conf_mode, "tau_max": cfg.tau_max, "tau_min": cfg.tau_min,
-                   "gamma": cfg.gamma, "D": cfg.D, "block_size": cfg.block_size,
+                   "gamma": cfg.gamma, "D": cfg.D, "block_size": cfg.block_size, "schedule": args.schedule,
                    "resident_logit_buffers": resident, "still_active_after": remaining, "anomalies": anomalies},
         "hbm_GBps_active_logits": elems * esz / seconds / 1e9,
         "pct_of_hbm_peak": 100.0 * elems * esz / seconds / 1e9 / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "kernel": "jot_vocab_reduce_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": measured_traffic(args.config, K) if args.dtype is None else None, "bytes_per_launch": k_bytes, "avg_launch_ms": k_sec * 1e3,
+                     "traffic": measured_traffic(args.config, K) if args.dtype is None and args.schedule == "none" else None, "bytes_per_launch": k_bytes, "avg_launch_ms": k_sec * 1e3,
                      "launch_ms": kms},
     }
     if not args.no_ceiling:

@@ -12,6 +12,8 @@
 #pragma once
 #include "jot_device.h"
 
+#define JOT_SCHED_CACHE 8          // keys per thread held in registers (rows up to 2048 examined)
+
 struct JotScheduleParams {
     int32_t B, L;
     float transfer_frac;
@@ -51,18 +53,39 @@ __global__ __launch_bounds__(JOT_WG) void jot_schedule_kernel(
         return;
 
     // key of entry j: bit pattern of p1, or 0 for a row without a softmax (conf is NaN there)
-    auto key_of = [&](int j) -> uint32_t {
+    auto load_key = [&](int j) -> uint32_t {
         const float c = last_conf[base + j];
         return (c == c) ? __float_as_uint(last_p1[base + j]) : 0u;
     };
+    // Rows of up to JOT_SCHED_CACHE * 256 examined positions keep their keys in registers
+    // (thread t holds entries t, t + 256, ...); longer rows re-read them from memory each pass.
+    constexpr int CACHE = JOT_SCHED_CACHE;
+    const bool cached = n <= CACHE * JOT_WG;
+    uint32_t kreg[CACHE];
+#pragma unroll
+    for (int c = 0; c < CACHE; ++c) {
+        const int j = c * JOT_WG + threadIdx.x;
+        kreg[c] = (cached && j < n) ? load_key(j) : 0u;
+    }
+    // number of entries with key >= lo (lo >= 1), counted with wave ballots; result in every thread
+    auto count_ge = [&](uint32_t lo) -> int {
+        int c = 0;
+        if (cached) {
+#pragma unroll
+            for (int q = 0; q < CACHE; ++q)
+                if (q * JOT_WG < n)
+                    c += __popcll(__ballot(kreg[q] >= lo)) * (lane == 0);
+        } else {
+            for (int j0 = 0; j0 < n; j0 += JOT_WG) {
+                const int j = j0 + threadIdx.x;
+                c += __popcll(__ballot(j < n && load_key(j) >= lo)) * (lane == 0);
+            }
+        }
+        return jot_wg_sum(c, lds);
+    };
 
     // how many to reveal
-    int cv = 0;
-    for (int j0 = 0; j0 < n; j0 += JOT_WG) {
-        const int j = j0 + threadIdx.x;
-        cv += __popcll(__ballot(j < n && key_of(j) != 0u)) * (lane == 0);
-    }
-    const int n_valid = jot_wg_sum(cv, lds);
+    const int n_valid = count_ge(1u);
     long long want = (n_transfer ? (long long)n_transfer[b] : 0ll) +
                      (long long)floor((double)prm.transfer_frac * (double)n);
     if (want > n_valid) want = n_valid;
@@ -70,26 +93,17 @@ __global__ __launch_bounds__(JOT_WG) void jot_schedule_kernel(
         return;
     const int k = (int)want;
 
-    // T = k-th largest key: the largest value with #(key >= T) >= k, built bit by bit
+    // T = k-th largest key: the largest value with #(key >= T) >= k, built bit by bit.
+    // When everything with a softmax is taken, T stays 0 (all their keys are >= 1 > T).
     uint32_t T = 0u;
     if (k < n_valid) {
-        for (int bit = 31; bit >= 0; --bit) {
+        for (int bit = 30; bit >= 0; --bit) {          // keys are positive floats: bit 31 is clear
             const uint32_t cand = T | (1u << bit);
-            int c = 0;
-            for (int j0 = 0; j0 < n; j0 += JOT_WG) {
-                const int j = j0 + threadIdx.x;
-                c += __popcll(__ballot(j < n && key_of(j) >= cand)) * (lane == 0);
-            }
-            if (jot_wg_sum(c, lds) >= k)
+            if (count_ge(cand) >= k)
                 T = cand;
         }
-    }                                  // else T = 0: every entry with a softmax (their keys are >= 1)
-    int cg = 0;
-    for (int j0 = 0; j0 < n; j0 += JOT_WG) {
-        const int j = j0 + threadIdx.x;
-        cg += __popcll(__ballot(j < n && key_of(j) > T)) * (lane == 0);
     }
-    const int n_above = jot_wg_sum(cg, lds);
+    const int n_above = (T == 0xffffffffu) ? 0 : count_ge(T + 1u);
     const int need_eq = k - n_above;   // entries equal to T still to take (0 when taking all)
 
     // take: key > T, and the first need_eq entries with key == T
@@ -97,7 +111,14 @@ __global__ __launch_bounds__(JOT_WG) void jot_schedule_kernel(
     for (int j0 = 0; j0 < n; j0 += JOT_WG) {
         const int j = j0 + threadIdx.x;
         const bool in = j < n;
-        const uint32_t key = in ? key_of(j) : 0u;
+        uint32_t key = 0u;
+        if (cached) {
+#pragma unroll
+            for (int q = 0; q < CACHE; ++q)
+                key = (j0 == q * JOT_WG) ? kreg[q] : key;
+        } else if (in) {
+            key = load_key(j);
+        }
         const bool above = in && key > T;
         const bool equal = in && key != 0u && key == T;
         const uint64_t m_eq = __ballot(equal);
