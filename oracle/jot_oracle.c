@@ -112,3 +112,37 @@ int jot_oracle_softmax_row(const void *row, int dtype, int32_t V, double *pi)
         pi[v] = st ? NAN : exp(widen(row, dtype, v) - m1) / S;
     return st;
 }
+
+/*
+ * Sampling-based finalization (Section 4.1, "Early-Exit Decision": the finalized token may be
+ * sampled from pi instead of taking the argmax).  Inverse-CDF sampling with a uniform number u
+ * in [0, 1) supplied by the caller: the token is the first index v whose cumulative probability
+ * pi_0 + ... + pi_v exceeds u.  If rounding leaves the total just below u, the last index with a
+ * non-zero probability is returned.  Also reports the cumulative probability just below and
+ * just above the chosen token (so a test can tell how far u is from either edge).
+ * Returns -1 for a row without a softmax.
+ */
+int32_t jot_oracle_sample_row(const void *row, int dtype, int32_t V, double u,
+                              double *cdf_below, double *cdf_above)
+{
+    int32_t a;
+    double m1, m2, S;
+    if (row_stats(row, dtype, V, &a, &m1, &m2, &S))
+        return -1;
+    double cum = 0.0;
+    int32_t last = -1;
+    for (int32_t v = 0; v < V; v++) {
+        double pv = exp(widen(row, dtype, v) - m1) / S;
+        if (pv > 0.0)
+            last = v;
+        if (cum + pv > u) {
+            *cdf_below = cum;
+            *cdf_above = cum + pv;
+            return v;
+        }
+        cum += pv;
+    }
+    *cdf_below = cum;
+    *cdf_above = cum;
+    return last;
+}

@@ -81,6 +81,9 @@ def _load():
         lib.jot_oracle_softmax_row.argtypes = [
             ctypes.c_void_p, ctypes.c_int, ctypes.c_int32, ctypes.c_void_p]
         lib.jot_oracle_softmax_row.restype = ctypes.c_int
+        lib.jot_oracle_sample_row.argtypes = [
+            ctypes.c_void_p, ctypes.c_int, ctypes.c_int32, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p]
+        lib.jot_oracle_sample_row.restype = ctypes.c_int32
         _lib = lib
     return _lib
 
@@ -116,6 +119,16 @@ def softmax_row(row: np.ndarray, dtype: int) -> np.ndarray:
     pi = np.zeros(row.shape[1], np.float64)
     _load().jot_oracle_softmax_row(row.ctypes.data, dtype, row.shape[1], pi.ctypes.data)
     return pi
+
+
+def sample_row(row: np.ndarray, dtype: int, u: float):
+    """Inverse-CDF sample of one row for the uniform number u: (token, cdf_below, cdf_above);
+    token = first index whose cumulative probability exceeds u.  -1 if the row has no softmax."""
+    row = _check_rows(row.reshape(1, -1), dtype)
+    lo, hi = ctypes.c_double(), ctypes.c_double()
+    v = _load().jot_oracle_sample_row(row.ctypes.data, dtype, row.shape[1], float(u),
+                                      ctypes.byref(lo), ctypes.byref(hi))
+    return int(v), lo.value, hi.value
 
 
 @dataclass
@@ -207,6 +220,9 @@ class StepRecord:
     exit: np.ndarray = None     # [A] bool: passed Eq. 6
     sched: np.ndarray = None    # [A] bool: picked by the transfer schedule
     k_row: np.ndarray = None    # [B] number of positions the schedule picked per batch row
+    final_token: np.ndarray = None  # [A] token written if finalized: argmax, or the sample
+    cdf_margin: np.ndarray = None   # [A] with sampling: distance of u from the nearer edge of the
+                                    #     chosen token's CDF interval (inf where nothing is sampled)
 
 
 @dataclass
@@ -235,10 +251,13 @@ class OracleState:
     def active_count(self) -> int:
         return int(self.active_list().size)
 
-    def evaluate(self, rows: np.ndarray, n_transfer=None, transfer_frac: float = 0.0) -> StepRecord:
+    def evaluate(self, rows: np.ndarray, n_transfer=None, transfer_frac: float = 0.0,
+                 sample_u=None) -> StepRecord:
         """Decisions of the next step for the given logit rows (rows[k] belongs to
         active_list()[k]) WITHOUT changing the state.  n_transfer ([B] ints) and transfer_frac
-        describe the transfer schedule of this step; by default it reveals nothing."""
+        describe the transfer schedule of this step; by default it reveals nothing.
+        sample_u: optional [B, L] uniform numbers in [0, 1); when given, a finalized position
+        takes a token sampled from pi (inverse CDF at sample_u[b, i]) instead of the argmax."""
         p = self.params
         act = self.active_list()
         if rows.shape[0] != act.size:
@@ -257,8 +276,17 @@ class OracleState:
             exit_ = ok & (conf >= tau)                          # Eq. 6
         sched, k_row = self._schedule(act, p1, ok, n_transfer, transfer_frac)
         commit = exit_ | sched                                  # logical OR, uncapped
+        final = a.copy()
+        margin = np.full(act.size, np.inf)
+        if sample_u is not None:
+            uflat = np.asarray(sample_u, np.float64).reshape(-1)
+            for k in np.flatnonzero(commit):
+                u = uflat[act[k]]
+                v, lo, hi = sample_row(rows[k], p.dtype, u)
+                final[k] = v
+                margin[k] = min(u - lo, hi - u)
         return StepRecord(self.step_index + 1, act, a, p1, p2, conf, tau, phi, commit, st,
-                          exit_, sched, k_row)
+                          exit_, sched, k_row, final, margin)
 
     def _schedule(self, act, p1, ok, n_transfer, transfer_frac):
         """Per batch row: the k positions with the largest p1 among the examined ones."""
@@ -289,19 +317,21 @@ class OracleState:
         for k in np.flatnonzero(rec.commit):                    # ascending b*L+i
             pos = int(rec.active[k])
             assert flat_msk[pos]
-            flat_tok[pos] = rec.token[k]
+            tok = rec.token[k] if rec.final_token is None else rec.final_token[k]
+            flat_tok[pos] = tok
             flat_msk[pos] = False
-            self.commit_log.append((rec.step, pos, int(rec.token[k])))
+            self.commit_log.append((rec.step, pos, int(tok)))
         self.anomalies += int(rec.status.sum())
 
-    def step(self, rows: np.ndarray, n_transfer=None, transfer_frac: float = 0.0) -> StepRecord:
-        rec = self.evaluate(rows, n_transfer, transfer_frac)
+    def step(self, rows: np.ndarray, n_transfer=None, transfer_frac: float = 0.0, sample_u=None) -> StepRecord:
+        rec = self.evaluate(rows, n_transfer, transfer_frac, sample_u)
         self.apply(rec)
         return rec
 
-    def step_full(self, logits: np.ndarray, n_transfer=None, transfer_frac: float = 0.0) -> StepRecord:
+    def step_full(self, logits: np.ndarray, n_transfer=None, transfer_frac: float = 0.0,
+                  sample_u=None) -> StepRecord:
         """Convenience for small cases: logits is the whole [B, L, V] array."""
         p = self.params
         act = self.active_list()
         rows = logits.reshape(p.B * p.L, p.V)[act]
-        return self.step(rows, n_transfer, transfer_frac)
+        return self.step(rows, n_transfer, transfer_frac, sample_u)
