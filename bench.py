@@ -138,6 +138,8 @@ def main():
     ap.add_argument("--schedule", choices=["none", "linear"], default="none",
                     help="also apply a transfer schedule each step: 'linear' reveals "
                          "remaining/steps_left of every row's examined positions (jot_step_scheduled)")
+    ap.add_argument("--sample", action="store_true",
+                    help="sampling-based finalization (jot_step_sampled with uniform numbers drawn beforehand)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
@@ -177,6 +179,9 @@ def main():
     resident = int(max(1, min(K, (free * 0.85) // buf_bytes)))
     bufs = [dgen.alloc_logits(poison=False) for _ in range(resident)]
     stream = torch.cuda.current_stream().cuda_stream
+    torch.manual_seed(cfg.seed)
+    uniforms = [torch.rand((cfg.B, cfg.L), dtype=torch.float32, device="cuda") for _ in range(resident)] \
+        if args.sample else None
 
     def fill_segment(g, first_step, count):
         """(untimed) logits of steps first_step .. first_step+count-1 for every position that is
@@ -199,8 +204,11 @@ def main():
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for k in range(seg):
-                if args.schedule == "linear":
-                    frac = 1.0 / max(1, cfg.steps - (done + k + 1) + 1)
+                frac = 1.0 / max(1, cfg.steps - (done + k + 1) + 1) if args.schedule == "linear" else 0.0
+                if args.sample:
+                    J.jot_step_sampled(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, 0, frac,
+                                       uniforms[k].data_ptr(), stream)
+                elif args.schedule == "linear":
                     J.jot_step_scheduled(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, 0, frac, stream)
                 else:
                     J.jot_step(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, stream)
@@ -240,13 +248,13 @@ def main():
         "config": {"workload": f"{cfg.name}: B={cfg.B}, L={cfg.L} ({cfg.gen_start} prompt + {cfg.n_gen} generated), "
                                f"V={cfg.V}, decode steps 1..{K}", "examined_positions_per_step": examined,
                    "conf_mode": cfg.conf_mode, "tau_max": cfg.tau_max, "tau_min": cfg.tau_min,
-                   "gamma": cfg.gamma, "D": cfg.D, "block_size": cfg.block_size, "schedule": args.schedule,
+                   "gamma": cfg.gamma, "D": cfg.D, "block_size": cfg.block_size, "schedule": args.schedule, "sampled_tokens": bool(args.sample),
                    "resident_logit_buffers": resident, "still_active_after": remaining, "anomalies": anomalies},
         "hbm_GBps_active_logits": elems * esz / seconds / 1e9,
         "pct_of_hbm_peak": 100.0 * elems * esz / seconds / 1e9 / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "kernel": "jot_vocab_reduce_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": measured_traffic(args.config, K) if args.dtype is None and args.schedule == "none" else None, "bytes_per_launch": k_bytes, "avg_launch_ms": k_sec * 1e3,
+                     "traffic": measured_traffic(args.config, K) if args.dtype is None and args.schedule == "none" and not args.sample else None, "bytes_per_launch": k_bytes, "avg_launch_ms": k_sec * 1e3,
                      "launch_ms": kms},
     }
     if not args.no_ceiling:

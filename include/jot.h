@@ -129,6 +129,22 @@ int jot_step(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t str
 int jot_step_scheduled(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
                        const int32_t* n_transfer_dev, float transfer_frac, void* stream);
 
+/*
+ * jot_step_scheduled with sampling-based finalization (Section 4.1, "Early-Exit Decision": the
+ * finalized token may be sampled from the predicted distribution instead of taking the argmax).
+ * Which positions are finalized is decided exactly as in jot_step_scheduled; a finalized position
+ * (b, i) gets the token drawn from pi by inverse-CDF sampling at the uniform number
+ * uniforms_dev[b*L + i]: the first vocabulary index whose cumulative probability exceeds it.
+ *   uniforms_dev : [B, L] float DEVICE array of numbers in [0, 1), drawn by the caller for this
+ *                  step; read only at finalized positions.  NULL = argmax finalization.
+ * Rows finalized in this step are read a second time (once per position over a whole decode).
+ * If rounding keeps the cumulative sum from exceeding the uniform number (a number within
+ * rounding of 1), the argmax token is kept.
+ */
+int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
+                     const int32_t* n_transfer_dev, float transfer_frac, const float* uniforms_dev,
+                     void* stream);
+
 /* Number of positions the NEXT step would examine (0 = decoding finished).  Waits for the work
  * enqueued so far on this state.  <0: JOT_ERR_*. */
 int64_t jot_active_count(jot_state* s);
@@ -158,6 +174,7 @@ const int32_t* jot_commit_log(jot_state* s, int64_t* n);
  */
 const int32_t* jot_examined_list(jot_state* s, int64_t* n);
 const int32_t* jot_last_token(const jot_state* s);
+const int32_t* jot_last_final_token(const jot_state* s);  /* token written if finalized: argmax or sample */
 const float*   jot_last_conf(const jot_state* s);
 const float*   jot_last_p1(const jot_state* s);
 const float*   jot_last_p2(const jot_state* s);

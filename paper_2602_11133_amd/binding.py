@@ -11,7 +11,7 @@ import numpy as np
 __all__ = [
     "JOT_F32", "JOT_BF16", "JOT_CONF_RATIO", "JOT_CONF_MAXPROB", "JOT_CONF_PROBGAP",
     "JotParams", "JotError", "load_library", "library_path",
-    "jot_workspace_bytes", "jot_init_state", "jot_step", "jot_step_scheduled", "jot_last_flags", "jot_active_count", "jot_step_index",
+    "jot_workspace_bytes", "jot_init_state", "jot_step", "jot_step_scheduled", "jot_step_sampled", "jot_last_flags", "jot_last_final_token", "jot_active_count", "jot_step_index",
     "jot_anomaly_count", "jot_tokens", "jot_masked", "jot_commit_step", "jot_active_list",
     "jot_commit_log", "jot_examined_list", "jot_last_token", "jot_last_conf", "jot_last_p1",
     "jot_last_p2", "jot_last_tau", "jot_profile_enable", "jot_profile_read", "jot_release",
@@ -64,7 +64,8 @@ def load_library():
         "jot_init_state": (ctypes.c_int, [ctypes.POINTER(vp), pp, vp, i64, vp, vp, vp]),
         "jot_step": (ctypes.c_int, [vp, vp, i64, i64, vp]),
         "jot_step_scheduled": (ctypes.c_int, [vp, vp, i64, i64, vp, ctypes.c_float, vp]),
-        "jot_last_flags": (vp, [vp]),
+        "jot_step_sampled": (ctypes.c_int, [vp, vp, i64, i64, vp, ctypes.c_float, vp, vp]),
+        "jot_last_flags": (vp, [vp]), "jot_last_final_token": (vp, [vp]),
         "jot_active_count": (i64, [vp]),
         "jot_step_index": (i32, [vp]),
         "jot_anomaly_count": (i64, [vp]),
@@ -120,6 +121,13 @@ def jot_step_scheduled(s: int, logits_dev: int, stride_b: int, stride_l: int, n_
                                              float(transfer_frac), stream), "jot_step_scheduled")
 
 
+def jot_step_sampled(s: int, logits_dev: int, stride_b: int, stride_l: int, n_transfer_dev: int,
+                     transfer_frac: float, uniforms_dev: int, stream: int = 0) -> None:
+    _check(load_library().jot_step_sampled(s, logits_dev, stride_b, stride_l, n_transfer_dev or None,
+                                           float(transfer_frac), uniforms_dev or None, stream),
+           "jot_step_sampled")
+
+
 def jot_active_count(s: int) -> int:
     return _check(load_library().jot_active_count(s), "jot_active_count")
 
@@ -149,6 +157,7 @@ def jot_last_p1(s: int) -> int: return _ptr("jot_last_p1", s)
 def jot_last_p2(s: int) -> int: return _ptr("jot_last_p2", s)
 def jot_last_tau(s: int) -> int: return _ptr("jot_last_tau", s)
 def jot_last_flags(s: int) -> int: return _ptr("jot_last_flags", s)
+def jot_last_final_token(s: int) -> int: return _ptr("jot_last_final_token", s)
 
 
 def jot_commit_log(s: int):

@@ -12,6 +12,7 @@
 #include "jot_compact.h"
 #include "jot_decide.h"
 #include "jot_device.h"
+#include "jot_sample.h"
 #include "jot_schedule.h"
 #include "jot_vocab_reduce.h"
 
@@ -30,7 +31,7 @@ constexpr int kItemsPerWg = 4;
 
 struct Layout {
     int64_t tokens, masked, commit_step, resolved_bits, active0, active1, counters, anomalies,
-        partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, row_block, row_n_active,
+        partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, last_m1, last_final, row_block, row_n_active,
         row_n_commit, commit_log, total;
     int64_t n_partials;
     int32_t words_per_row;
@@ -78,6 +79,8 @@ Layout make_layout(const jot_params* p, int target_items)
     l.last_p2 = take(n * 4);
     l.last_tau = take(n * 4);
     l.last_flags = take(n);
+    l.last_m1 = take(n * 4);
+    l.last_final = take(n * 4);
     l.row_block = take((int64_t)p->B * 4);
     l.row_n_active = take((int64_t)p->B * 4);
     l.row_n_commit = take((int64_t)p->B * 4);
@@ -97,6 +100,7 @@ struct jot_state {
     int cur;                    // which counter block / active list the next step reads
     int32_t step;
     int grid_reduce;
+    int grid_sample;
     int target_items;
     JotDecideParams decide;
     JotCompactParams compact;
@@ -191,6 +195,7 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
         if (v >= 1 && v <= kMaxWgPerCu) occ = v;
     }
     s->grid_reduce = cus * occ;
+    s->grid_sample = cus * 4;
     s->target_items = s->grid_reduce * kItemsPerWg;
     if (s->target_items > max_target_items()) s->target_items = max_target_items();
     s->lay = make_layout(p, max_target_items());
@@ -259,7 +264,15 @@ int jot_step(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t str
 int jot_step_scheduled(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
                        const int32_t* n_transfer_dev, float transfer_frac, void* stream)
 {
+    return jot_step_sampled(s, logits_dev, stride_b, stride_l, n_transfer_dev, transfer_frac, nullptr, stream);
+}
+
+int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
+                     const int32_t* n_transfer_dev, float transfer_frac, const float* uniforms_dev,
+                     void* stream)
+{
     if (!s || !logits_dev) return JOT_ERR_NULL_POINTER;
+    if (reinterpret_cast<uintptr_t>(uniforms_dev) % 4) return JOT_ERR_MISALIGNED;
     if (!(transfer_frac >= 0.0f && transfer_frac <= 1.0f)) return JOT_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(n_transfer_dev) % 4) return JOT_ERR_MISALIGNED;
     const jot_params& p = s->p;
@@ -301,7 +314,9 @@ int jot_step_scheduled(jot_state* s, const void* logits_dev, int64_t stride_b, i
                        s->at<int32_t>(s->lay.commit_step), s->at<int32_t>(s->lay.last_token),
                        s->at<float>(s->lay.last_conf), s->at<float>(s->lay.last_p1),
                        s->at<float>(s->lay.last_p2), s->at<float>(s->lay.last_tau),
-                       s->at<uint8_t>(s->lay.last_flags), s->at<unsigned long long>(s->lay.anomalies));
+                       s->at<uint8_t>(s->lay.last_flags), s->at<float>(s->lay.last_m1),
+                       s->at<int32_t>(s->lay.last_final),
+                       s->at<unsigned long long>(s->lay.anomalies));
     if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     if (n_transfer_dev || transfer_frac > 0.0f) {
         JotScheduleParams sp;
@@ -311,6 +326,20 @@ int jot_step_scheduled(jot_state* s, const void* logits_dev, int64_t stride_b, i
                            s->at<float>(s->lay.last_conf), s->at<int32_t>(s->lay.last_token),
                            s->at<uint8_t>(s->lay.last_flags), s->at<int32_t>(s->lay.tokens),
                            s->at<int32_t>(s->lay.commit_step));
+        if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
+    }
+    if (uniforms_dev) {
+        const int grid = s->grid_sample;
+        if (p.dtype == JOT_F32)
+            hipLaunchKernelGGL(jot_sample_kernel<JotF32>, dim3(grid), dim3(JOT_WG), 0, st, logits_dev, stride_b,
+                               stride_l, p.L, p.V, s->active(in), s->counters(in), s->at<uint8_t>(s->lay.last_flags),
+                               s->at<float>(s->lay.last_m1), uniforms_dev,
+                               s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.last_final));
+        else
+            hipLaunchKernelGGL(jot_sample_kernel<JotBF16>, dim3(grid), dim3(JOT_WG), 0, st, logits_dev, stride_b,
+                               stride_l, p.L, p.V, s->active(in), s->counters(in), s->at<uint8_t>(s->lay.last_flags),
+                               s->at<float>(s->lay.last_m1), uniforms_dev,
+                               s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.last_final));
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     }
     s->step = step;
@@ -351,6 +380,7 @@ const int32_t* jot_examined_list(jot_state* s, int64_t* n)
 }
 
 const int32_t* jot_last_token(const jot_state* s) { return s ? s->at<int32_t>(s->lay.last_token) : nullptr; }
+const int32_t* jot_last_final_token(const jot_state* s) { return s ? s->at<int32_t>(s->lay.last_final) : nullptr; }
 const float* jot_last_conf(const jot_state* s) { return s ? s->at<float>(s->lay.last_conf) : nullptr; }
 const float* jot_last_p1(const jot_state* s) { return s ? s->at<float>(s->lay.last_p1) : nullptr; }
 const float* jot_last_p2(const jot_state* s) { return s ? s->at<float>(s->lay.last_p2) : nullptr; }

@@ -27,6 +27,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_decide_kernel(
     int32_t* __restrict__ tokens, int32_t* __restrict__ commit_step,
     int32_t* __restrict__ last_token, float* __restrict__ last_conf, float* __restrict__ last_p1,
     float* __restrict__ last_p2, float* __restrict__ last_tau, uint8_t* __restrict__ last_flags,
+    float* __restrict__ last_m1, int32_t* __restrict__ last_final,
     unsigned long long* __restrict__ anomalies)
 {
     const int64_t n_active = counters->n_active;
@@ -90,6 +91,8 @@ __global__ __launch_bounds__(JOT_WG) void jot_decide_kernel(
     if (!has_softmax)
         atomicAdd(anomalies, 1ull);
     last_token[r] = idx;
+    last_final[r] = idx;            // the sampling kernel, if it runs, overwrites this
+    last_m1[r] = m1;
     last_flags[r] = commit ? 1 : 0;
     last_conf[r] = has_softmax ? conf : __uint_as_float(0x7fc00000u);
     last_p1[r] = p1;

@@ -43,9 +43,18 @@ class GpuJot:
         except Exception:
             pass
 
-    def step(self, logits: torch.Tensor, stride_b=None, stride_l=None, n_transfer=None, transfer_frac=0.0):
+    def step(self, logits: torch.Tensor, stride_b=None, stride_l=None, n_transfer=None, transfer_frac=0.0,
+             uniforms=None):
         sb = logits.stride(0) if stride_b is None else stride_b
         sl = logits.stride(1) if stride_l is None else stride_l
+        if uniforms is not None:
+            self._u = torch.from_numpy(np.ascontiguousarray(uniforms, np.float32)).to(self.dev)
+            nt = 0
+            if n_transfer is not None:
+                self._nt = torch.from_numpy(np.ascontiguousarray(n_transfer, np.int32)).to(self.dev)
+                nt = self._nt.data_ptr()
+            J.jot_step_sampled(self.h, logits.data_ptr(), sb, sl, nt, transfer_frac, self._u.data_ptr(), self.stream)
+            return
         if n_transfer is None and transfer_frac == 0.0:
             J.jot_step(self.h, logits.data_ptr(), sb, sl, self.stream)
             return
@@ -86,6 +95,7 @@ class GpuJot:
         for name in ("conf", "p1", "p2", "tau"):
             out[name] = J.device_to_host(getattr(J, "jot_last_" + name)(self.h), n, np.float32)
         out["flags"] = J.device_to_host(J.jot_last_flags(self.h), n, np.uint8)
+        out["final"] = J.device_to_host(J.jot_last_final_token(self.h), n, np.int32)
         return out
 
 
@@ -134,3 +144,5 @@ def compare_step(gpu_last: dict, rec, act_full: np.ndarray, tol: float, select=N
     np.testing.assert_array_equal((g["flags"] & 1).astype(bool), want_exit)
     want_sched = rec.sched if rec.sched is not None else np.zeros_like(rec.commit)
     np.testing.assert_array_equal((g["flags"] & 2).astype(bool), want_sched)
+    want_final = rec.final_token if rec.final_token is not None else rec.token
+    np.testing.assert_array_equal(g["final"][rec.commit], want_final[rec.commit])   # bit exact

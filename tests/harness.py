@@ -12,6 +12,8 @@ from gen.trajectory import Trajectory
 from oracle import jot_oracle as O
 
 GUARD = 1e-4          # |conf - tau| >= GUARD * max(1, |tau|) for every examined position
+GUARD_U = 1e-6        # sampling: the uniform number stays this far (in probability) from both
+                      # edges of the chosen token's CDF interval
 MAX_BUMPS = 200
 
 
@@ -63,11 +65,18 @@ class LockstepRun:
     def active_full(self) -> np.ndarray:
         return self.to_full(self.state.active_list())
 
-    def next_step(self, n_transfer=None, transfer_frac: float = 0.0):
+    def draw_uniforms(self, step: int) -> np.ndarray:
+        """[B, L] float32 uniform numbers in [0, 1) for sampling-based finalization at this step."""
+        rng = np.random.default_rng([self.cfg.seed, 0x756E6966, step])
+        return rng.random((self.cfg.B, self.cfg.L), dtype=np.float32)
+
+    def next_step(self, n_transfer=None, transfer_frac: float = 0.0, sample_u=None):
         """Advance the oracle one step.  Returns (rec, T, R, rows) where rec.active is in
         sub-batch numbering, T/R are the final planted tables of this step (full canvas) and
         rows are the logit rows the oracle saw (a view valid until the next call).
-        n_transfer ([B] of the FULL batch) / transfer_frac: the step's transfer schedule."""
+        n_transfer ([B] of the FULL batch) / transfer_frac: the step's transfer schedule.
+        sample_u ([B, L] float32 of the FULL batch, modified in place where a number has to be
+        redrawn to stay clear of a CDF edge): sampling-based finalization."""
         if n_transfer is not None:
             n_transfer = np.asarray(n_transfer)[self.batch_rows]
         st, tr = self.state, self.traj
@@ -75,9 +84,21 @@ class LockstepRun:
         act_full = self.active_full()
         T, R = tr.planted(n)
         rows = self.gen.rows(n, act_full, T, R)
-        rec = st.evaluate(rows, n_transfer, transfer_frac)
+        u_sub = None if sample_u is None else sample_u[self.batch_rows]
+        redraw = np.random.default_rng([self.cfg.seed, 0x72656472, n])
+        rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub)
         for _ in range(MAX_BUMPS):
             bad = too_close(rec, self.cfg.L)
+            if sample_u is not None:
+                edge = np.flatnonzero(rec.commit & (rec.cdf_margin < GUARD_U))
+                if edge.size:                   # a new uniform number for that position (an input)
+                    for k in edge:
+                        bb, ii = divmod(int(act_full[k]), self.cfg.L)
+                        sample_u[bb, ii] = redraw.random(dtype=np.float32)
+                    u_sub = sample_u[self.batch_rows]
+                    if bad.size == 0:
+                        rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub)
+                        continue
             if bad.size == 0:
                 break
             for k in bad:
@@ -86,7 +107,7 @@ class LockstepRun:
             T, R = tr.planted(n)
             fixer = HostGenerator(self.cfg, tr.target, tr.rival, 1)
             rows[bad] = fixer.rows(n, act_full[bad], T, R)
-            rec = st.evaluate(rows, n_transfer, transfer_frac)
+            rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub)
         else:
             raise RuntimeError("could not clear the guard band")
         st.apply(rec)

@@ -10,7 +10,7 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 from gen.bf16 import bf16_bits_to_f32, f32_to_bf16_bits  # noqa: E402
-from harness import GUARD, too_close  # noqa: E402
+from harness import GUARD, GUARD_U, too_close  # noqa: E402
 from oracle import jot_oracle as O  # noqa: E402
 
 
@@ -64,8 +64,10 @@ def to_device(logits: np.ndarray, dtype: int, stride_l: int):
 
 
 def check_case(gpu, p: O.OracleParams, tokens, masked, logit_seq, stride_pad=0, tol=None, clear=True,
-               schedule=None):
-    """schedule: optional list of (n_transfer, frac) per step."""
+               schedule=None, uniforms=None):
+    """schedule: optional list of (n_transfer, frac) per step.  uniforms: optional list of [B, L]
+    float32 arrays per step (sampling-based finalization); numbers that fall within GUARD_U of
+    an edge of the chosen token's CDF interval are redrawn here (they are inputs)."""
     import paper_2602_11133_amd as J
     esz = 4 if p.dtype == O.F32 else 2
     align = 16 // esz
@@ -91,9 +93,20 @@ def check_case(gpu, p: O.OracleParams, tokens, masked, logit_seq, stride_pad=0, 
             if p.dtype == O.BF16:
                 assert np.array_equal(bf16_bits_to_f32(f32_to_bf16_bits(logits)).reshape(logits.shape), logits)
         act = st.active_list()
-        rec = st.step(as_rows(logits.reshape(p.B * p.L, p.V)[act], p.dtype), nt, frac)
+        u = None
+        if uniforms is not None:
+            u = np.array(uniforms[n - 1], np.float32)
+            redraw = np.random.default_rng(1000 + n)
+            for _ in range(100):
+                probe = st.evaluate(as_rows(logits.reshape(p.B * p.L, p.V)[act], p.dtype), nt, frac, u)
+                edge = np.flatnonzero(probe.commit & (probe.cdf_margin < GUARD_U))
+                if edge.size == 0:
+                    break
+                for k in edge:
+                    u.reshape(-1)[act[k]] = redraw.random(dtype=np.float32)
+        rec = st.step(as_rows(logits.reshape(p.B * p.L, p.V)[act], p.dtype), nt, frac, u)
         dev = to_device(logits, p.dtype, stride_l)
-        g.step(dev, stride_b=p.L * stride_l, stride_l=stride_l, n_transfer=nt, transfer_frac=frac)
+        g.step(dev, stride_b=p.L * stride_l, stride_l=stride_l, n_transfer=nt, transfer_frac=frac, uniforms=u)
         gpu.compare_step(g.last(), rec, act, tol)
         np.testing.assert_array_equal(g.tokens(), st.tokens)
         np.testing.assert_array_equal(g.masked(), st.masked)
@@ -294,3 +307,37 @@ def test_schedule_on_a_long_row(gpu):
     p, tokens, masked, seq = random_case(47, B=2, L=2500, V=48, gs=3, conf_mode=O.CONF_MAXPROB, tau_max=0.95,
                                          tau_min=0.0, gamma=0.5, D=8, steps=3)
     check_case(gpu, p, tokens, masked, seq, schedule=[([1, 1999], 0.0), (None, 0.37), ([5, 5], 0.5)])
+
+
+# --------------------------------------------------------------------------- sampling-based finalization
+
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+@pytest.mark.parametrize("V", [2, 9, 1003, 8192, 8200, 40_003])
+def test_sampled_tokens(gpu, dtype, V):
+    say(f"[edge] sampling V={V} dtype={dtype}")
+    # flat-ish rows (scale 1.5) so that samples differ from the argmax; tau = 0: everything is finalized
+    rng = np.random.default_rng(V + dtype)
+    B, L = 2, 23
+    p = O.OracleParams(B=B, L=L, V=V, dtype=dtype, conf_mode=O.CONF_MAXPROB, tau_max=0.0, tau_min=0.0, D=0)
+    lg = (rng.standard_normal((B, L, V)) * 1.5).astype(np.float32)
+    lg[0, 3, : V // 2] = -np.inf                       # zero-probability prefix
+    lg[1, 4, :] = -30.0
+    lg[1, 4, V - 1] = 5.0                              # all the mass on the last token (ragged tail when V % 8 != 0)
+    lg[1, 5, :] = -30.0
+    lg[1, 5, 0] = 5.0                                  # all the mass on the first token
+    u = rng.random((B, L), dtype=np.float32)
+    u[0, 0], u[0, 1], u[0, 2] = 0.0, 1e-7, 0.9999999   # extremes
+    toks, msk, log, last = check_case(gpu, p, np.zeros((B, L), np.int32), np.ones((B, L), bool), [lg],
+                                      clear=False, uniforms=[u])
+    assert not msk.any()
+    assert toks[1, 4] == V - 1 and toks[1, 5] == 0 and toks[0, 3] >= V // 2
+    if V > 100:
+        assert (last["final"] != last["token"]).mean() > 0.3      # sampling really differs from argmax
+
+
+def test_sampling_leaves_unfinalized_positions_alone(gpu):
+    p, tokens, masked, seq = random_case(51, B=2, L=60, V=500, gs=8, conf_mode=O.CONF_RATIO, tau_max=50.0,
+                                         tau_min=1.0, gamma=0.5, D=8, steps=5)
+    rng = np.random.default_rng(52)
+    us = [rng.random((2, 60), dtype=np.float32) for _ in range(5)]
+    check_case(gpu, p, tokens, masked, seq, uniforms=us, schedule=[([1, 2], 0.0)] * 5)

@@ -34,7 +34,7 @@ def gpu():
     return gpu_harness
 
 
-def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True, schedule=None):
+def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True, schedule=None, sample=False):
     """Lock-step decode: oracle on the host (optionally on a subset of batch rows), library on
     the GPU over the whole batch; compares every step and the final state."""
     from gen.device import DeviceGenerator
@@ -56,14 +56,15 @@ def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True, s
         act_full = run.active_full()
         nt, frac = schedule(n) if schedule else (None, 0.0)
         frac = float(np.float32(frac))
-        rec, T, R, rows = run.next_step(nt, frac)
+        u = run.draw_uniforms(n) if sample else None
+        rec, T, R, rows = run.next_step(nt, frac, u)
         n_gpu = g.active_count()
         if use_device_gen:
             dgen.set_planted(T, R)
             dgen.fill(logits, n, J.jot_active_list(g.h), n_gpu)
         else:
             gpu.upload_rows(logits, act_full, rows, cfg.dtype)
-        g.step(logits, n_transfer=nt, transfer_frac=frac)
+        g.step(logits, n_transfer=nt, transfer_frac=frac, uniforms=u)
         last = g.last()
         sel = followed[last["active"] // cfg.L] if batch_rows is not None else None
         gpu.compare_step(last, rec, act_full, TOL[cfg.dtype], sel)
@@ -196,3 +197,20 @@ def test_config4_with_one_token_per_step_schedule(gpu):
 def test_config5_ratio_with_schedule_short(gpu):
     cfg = CONFIGS[5].replace(B=4, steps=24)
     run_parity(gpu, cfg, batch_rows=[1, 2], max_steps=24, schedule=lambda n: (np.full(cfg.B, 8, np.int32), 0.02))
+
+
+# --------------------------------------------------------------------------- sampling-based finalization
+
+def test_config1_sampled(gpu):
+    assert run_parity(gpu, CONFIGS[1], max_steps=1, sample=True) == 1
+
+
+def test_config2_sampled_with_schedule(gpu):
+    cfg = CONFIGS[2].replace(steps=32, L=64 + 128)
+    run_parity(gpu, cfg, sample=True, schedule=lambda n: (None, 1.0 / max(1, cfg.steps - n + 1)))
+
+
+def test_config5_sampled_short(gpu):
+    cfg = CONFIGS[5].replace(B=4, steps=16)
+    run_parity(gpu, cfg, batch_rows=[0, 3], max_steps=16, sample=True,
+               schedule=lambda n: (np.full(cfg.B, 16, np.int32), 0.0))
