@@ -31,7 +31,7 @@ constexpr int kItemsPerWg = 4;
 
 struct Layout {
     int64_t tokens, masked, commit_step, resolved_bits, active0, active1, counters, anomalies,
-        partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, last_m1, last_final, row_block, row_n_active,
+        partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, last_m1, last_final, sample_list, sample_count, row_block, row_n_active,
         row_n_commit, commit_log, total;
     int64_t n_partials;
     int32_t words_per_row;
@@ -81,6 +81,8 @@ Layout make_layout(const jot_params* p, int target_items)
     l.last_flags = take(n);
     l.last_m1 = take(n * 4);
     l.last_final = take(n * 4);
+    l.sample_list = take(n * 4);
+    l.sample_count = take(4);
     l.row_block = take((int64_t)p->B * 4);
     l.row_n_active = take((int64_t)p->B * 4);
     l.row_n_commit = take((int64_t)p->B * 4);
@@ -132,7 +134,8 @@ int enqueue_compaction(jot_state* s, int32_t step, hipStream_t st)
                        s->at<int32_t>(s->lay.row_n_active), s->at<int32_t>(s->lay.row_n_commit),
                        s->counters(in), s->counters(out), s->active(out),
                        s->at<int32_t>(s->lay.commit_log), s->at<uint64_t>(s->lay.resolved_bits),
-                       s->at<unsigned long long>(s->lay.anomalies), s->host_dev);
+                       s->at<unsigned long long>(s->lay.anomalies), s->host_dev,
+                       s->at<int32_t>(s->lay.sample_count));
     if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     // the kernel above also wrote the new counters into pinned host memory; the host waits on this
     if (hipEventRecord(s->done, st) != hipSuccess) return JOT_ERR_HIP;
@@ -316,6 +319,8 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
                        s->at<float>(s->lay.last_p2), s->at<float>(s->lay.last_tau),
                        s->at<uint8_t>(s->lay.last_flags), s->at<float>(s->lay.last_m1),
                        s->at<int32_t>(s->lay.last_final),
+                       uniforms_dev ? s->at<int32_t>(s->lay.sample_list) : nullptr,
+                       s->at<int32_t>(s->lay.sample_count),
                        s->at<unsigned long long>(s->lay.anomalies));
     if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     if (n_transfer_dev || transfer_frac > 0.0f) {
@@ -325,20 +330,22 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
                            s->active(in), s->at<int32_t>(s->lay.row_n_active), s->at<float>(s->lay.last_p1),
                            s->at<float>(s->lay.last_conf), s->at<int32_t>(s->lay.last_token),
                            s->at<uint8_t>(s->lay.last_flags), s->at<int32_t>(s->lay.tokens),
-                           s->at<int32_t>(s->lay.commit_step));
+                           s->at<int32_t>(s->lay.commit_step),
+                           uniforms_dev ? s->at<int32_t>(s->lay.sample_list) : nullptr,
+                           s->at<int32_t>(s->lay.sample_count));
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     }
     if (uniforms_dev) {
         const int grid = s->grid_sample;
         if (p.dtype == JOT_F32)
             hipLaunchKernelGGL(jot_sample_kernel<JotF32>, dim3(grid), dim3(JOT_WG), 0, st, logits_dev, stride_b,
-                               stride_l, p.L, p.V, s->active(in), s->counters(in), s->at<uint8_t>(s->lay.last_flags),
-                               s->at<float>(s->lay.last_m1), uniforms_dev,
+                               stride_l, p.L, p.V, s->active(in), s->at<int32_t>(s->lay.sample_list),
+                               s->at<int32_t>(s->lay.sample_count), s->at<float>(s->lay.last_m1), uniforms_dev,
                                s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.last_final));
         else
             hipLaunchKernelGGL(jot_sample_kernel<JotBF16>, dim3(grid), dim3(JOT_WG), 0, st, logits_dev, stride_b,
-                               stride_l, p.L, p.V, s->active(in), s->counters(in), s->at<uint8_t>(s->lay.last_flags),
-                               s->at<float>(s->lay.last_m1), uniforms_dev,
+                               stride_l, p.L, p.V, s->active(in), s->at<int32_t>(s->lay.sample_list),
+                               s->at<int32_t>(s->lay.sample_count), s->at<float>(s->lay.last_m1), uniforms_dev,
                                s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.last_final));
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     }

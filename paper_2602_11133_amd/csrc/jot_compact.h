@@ -97,7 +97,8 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
     const int32_t* __restrict__ row_n_commit, const JotCounters* __restrict__ cnt_in,
     JotCounters* __restrict__ cnt_out, int32_t* __restrict__ active_out,
     int32_t* __restrict__ commit_log, uint64_t* __restrict__ resolved_bits,
-    const unsigned long long* __restrict__ anomalies, JotHostBlock* __restrict__ host_out)
+    const unsigned long long* __restrict__ anomalies, JotHostBlock* __restrict__ host_out,
+    int32_t* __restrict__ sample_count)
 {
     __shared__ int lds[JOT_WAVES];
     __shared__ int wave_act[JOT_WAVES], wave_com[JOT_WAVES];
@@ -167,6 +168,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
         host_out->c.n_examined = cnt_in->n_active;
         host_out->c.reserved = 0;
         host_out->anomalies = *anomalies;
+        *sample_count = 0;            // the sampling work list of this step has been consumed
         __threadfence_system();
     }
 }

@@ -28,6 +28,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_decide_kernel(
     int32_t* __restrict__ last_token, float* __restrict__ last_conf, float* __restrict__ last_p1,
     float* __restrict__ last_p2, float* __restrict__ last_tau, uint8_t* __restrict__ last_flags,
     float* __restrict__ last_m1, int32_t* __restrict__ last_final,
+    int32_t* __restrict__ sample_list, int32_t* __restrict__ sample_count,   // NULL unless sampling
     unsigned long long* __restrict__ anomalies)
 {
     const int64_t n_active = counters->n_active;
@@ -87,6 +88,8 @@ __global__ __launch_bounds__(JOT_WG) void jot_decide_kernel(
     if (commit) {
         tokens[pos] = idx;
         commit_step[pos] = step;
+        if (sample_list)        // unordered work list for the sampling kernel (rows are independent)
+            sample_list[atomicAdd(sample_count, 1)] = (int32_t)r;
     }
     if (!has_softmax)
         atomicAdd(anomalies, 1ull);

@@ -5,7 +5,9 @@
 // is the first vocabulary index whose cumulative probability exceeds u, i.e. the first v with
 //     sum_{w <= v} exp(l_w - m1)  >  u * S,          S = sum_w exp(l_w - m1)  (from the reduction).
 // Only rows that were finalized this step are read again (each position is finalized once per
-// decode, so over a whole decode this re-reads every row at most once).
+// decode, so over a whole decode this re-reads every row a few times at most).  The deciding
+// kernels append those rows to a work list (in arrival order: rows are independent, the result
+// does not depend on it) and this kernel deals the list out to its workgroups.
 //
 // One workgroup per finalized row.  The exponentials are binary32 (v_exp_f32), every sum is
 // accumulated in double, and the threshold u * S uses the kernel's own total S of the same
@@ -42,8 +44,8 @@ __device__ __forceinline__ double jot_wg_total(double v, double* lds)   // every
 template <class T>
 __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
     const void* __restrict__ logits, int64_t stride_b, int64_t stride_l, int L, int V,
-    const int32_t* __restrict__ active, const JotCounters* __restrict__ counters,
-    const uint8_t* __restrict__ last_flags, const float* __restrict__ last_m1,
+    const int32_t* __restrict__ active, const int32_t* __restrict__ sample_list,
+    const int32_t* __restrict__ sample_count, const float* __restrict__ last_m1,
     const float* __restrict__ uniforms, int32_t* __restrict__ tokens, int32_t* __restrict__ last_final)
 {
     constexpr int VEC = T::VEC;
@@ -52,12 +54,11 @@ __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
     __shared__ double lds[JOT_WAVES];
     __shared__ double wave_tot[JOT_WAVES];
     __shared__ int found_token;
-    const int64_t n_active = counters->n_active;
+    const int n_items = *sample_count;            // rows finalized this step, listed by the kernels before
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    for (int64_t r = blockIdx.x; r < n_active; r += gridDim.x) {
-        if (last_flags[r] == 0)
-            continue;                                            // uniform: r is per workgroup
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int r = sample_list[item];
         const int pos = active[r];
         const int b = pos / L, i = pos - b * L;
         const char* row = reinterpret_cast<const char*>(logits) +

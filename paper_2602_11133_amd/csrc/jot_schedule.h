@@ -35,7 +35,8 @@ __global__ __launch_bounds__(JOT_WG) void jot_schedule_kernel(
     const int32_t* __restrict__ active, const int32_t* __restrict__ row_n_active,
     const float* __restrict__ last_p1, const float* __restrict__ last_conf,
     const int32_t* __restrict__ last_token, uint8_t* __restrict__ last_flags,
-    int32_t* __restrict__ tokens, int32_t* __restrict__ commit_step)
+    int32_t* __restrict__ tokens, int32_t* __restrict__ commit_step,
+    int32_t* __restrict__ sample_list, int32_t* __restrict__ sample_count)   // NULL unless sampling
 {
     __shared__ int lds[JOT_WAVES];
     __shared__ int wave_eq[JOT_WAVES];
@@ -139,6 +140,8 @@ __global__ __launch_bounds__(JOT_WG) void jot_schedule_kernel(
             if (commit_step[pos] != step) {          // not already finalized by the early exit
                 tokens[pos] = last_token[r];
                 commit_step[pos] = step;
+                if (sample_list)
+                    sample_list[atomicAdd(sample_count, 1)] = (int32_t)r;
             }
         }
         run_eq += tot;
