@@ -121,9 +121,17 @@ def cpu_baseline(cfg, traj, sample_rows: int):
     rec = st.evaluate(rows)
     dt = time.perf_counter() - t0
     assert rec.active.size == act.size
+    # the same oracle on one thread, on the first batch row only
+    one = O.OracleState.init(oracle_params(cfg.replace(B=1)), tokens[:1], masked[:1], threads=1)
+    n1 = one.active_list().size
+    t0 = time.perf_counter()
+    one.evaluate(rows[:n1])
+    dt1 = time.perf_counter() - t0
     return {"value": act.size * cfg.V / dt, "unit": "positions·vocab/s", "cores": threads, "kind": "oracle",
             "sample": f"step 1, batch rows 0-{len(rows_b) - 1} ({act.size} positions x V={cfg.V}), "
-                      f"{dt:.2f} s wall on {threads} threads", "seconds": dt}
+                      f"{dt:.2f} s wall on {threads} threads", "seconds": dt,
+            "single_thread_value": n1 * cfg.V / dt1,
+            "single_thread_sample": f"step 1, batch row 0 ({n1} positions), {dt1:.2f} s on 1 thread"}
 
 
 def main():
