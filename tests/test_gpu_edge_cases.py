@@ -341,3 +341,89 @@ def test_sampling_leaves_unfinalized_positions_alone(gpu):
     rng = np.random.default_rng(52)
     us = [rng.random((2, 60), dtype=np.float32) for _ in range(5)]
     check_case(gpu, p, tokens, masked, seq, uniforms=us, schedule=[([1, 2], 0.0)] * 5)
+
+
+# --------------------------------------------------------------------------- sizes, streams, run-time errors
+
+def test_very_long_vocabulary_single_rows(gpu):
+    # one row of 3 000 001 logits (12 MB): many pieces per row, 64-bit-safe index arithmetic, ragged end
+    B, L, V = 1, 3, 3_000_001
+    rng = np.random.default_rng(61)
+    p = O.OracleParams(B=B, L=L, V=V, dtype=O.F32, conf_mode=O.CONF_RATIO, tau_max=20.0, tau_min=1.0, D=1)
+    lg = rng.standard_normal((B, L, V)).astype(np.float32)
+    lg[0, 0, V - 1] = 12.0
+    lg[0, 1, 1_500_000] = 11.0
+    lg[0, 2, 0] = 2.0
+    toks, msk, log, last = check_case(gpu, p, np.zeros((B, L), np.int32), np.ones((B, L), bool), [lg])
+    assert toks[0, 0] == V - 1 and toks[0, 1] == 1_500_000
+
+
+def test_large_canvas_with_few_masked_positions(gpu):
+    # 1.5 million canvas positions, about 1 % masked, scattered: frozen positions cost nothing
+    B, L, V = 300, 5000, 24
+    rng = np.random.default_rng(62)
+    p = O.OracleParams(B=B, L=L, V=V, dtype=O.BF16, conf_mode=O.CONF_MAXPROB, tau_max=0.5, tau_min=0.0,
+                       gamma=0.7, D=16, gen_start=100)
+    masked = rng.random((B, L)) < 0.01
+    masked[:, :100] = False
+    tokens = rng.integers(0, V, (B, L)).astype(np.int32)
+    seq = [np.round(rng.standard_normal((B, L, V)) * 8) / 4 for _ in range(2)]
+    check_case(gpu, p, tokens, masked, seq)
+
+
+def test_step_argument_errors_have_no_effect(gpu):
+    import paper_2602_11133_amd as J
+    p, tokens, masked, seq = random_case(63, B=2, L=20, V=100, gs=4, conf_mode=O.CONF_RATIO, tau_max=5.0,
+                                         tau_min=1.0, gamma=0.5, D=4, steps=1)
+    jp = J.JotParams(B=2, L=20, V=100, dtype=0, conf_mode=0, tau_max=5.0, tau_min=1.0, gamma=0.5, D=4,
+                     eps=1e-12, gen_start=4, block_size=0)
+    g = gpu.GpuJot(jp, tokens, masked)
+    dev = to_device(seq[0], O.F32, 100)
+    before = (g.tokens().copy(), g.masked().copy(), g.active_list().copy())
+    lib = J.load_library()
+    st = g.stream
+    assert lib.jot_step(g.h, dev.data_ptr(), 2000, 99, st) == -1            # stride_l < V
+    assert lib.jot_step(g.h, dev.data_ptr(), 1000, 100, st) == -1           # rows of different batches overlap
+    assert lib.jot_step(g.h, dev.data_ptr() + 4, 2000, 100, st) == -5       # misaligned base
+    assert lib.jot_step(g.h, dev.data_ptr(), 2048, 102, st) == -5           # misaligned row stride
+    assert lib.jot_step(g.h, None, 2000, 100, st) == -2
+    assert lib.jot_step_scheduled(g.h, dev.data_ptr(), 2000, 100, None, 1.5, st) == -1
+    assert lib.jot_step_scheduled(g.h, dev.data_ptr(), 2000, 100, None, float("nan"), st) == -1
+    assert J.jot_step_index(g.h) == 0
+    np.testing.assert_array_equal(g.tokens(), before[0])
+    np.testing.assert_array_equal(g.masked(), before[1])
+    np.testing.assert_array_equal(g.active_list(), before[2])
+    g.close()
+
+
+def test_two_states_interleaved_on_a_side_stream(gpu):
+    # two independent decodes stepped alternately on a non-default stream
+    import paper_2602_11133_amd as J
+    cases = [random_case(64 + k, B=2, L=50, V=700, gs=6, conf_mode=O.CONF_RATIO, tau_max=10.0, tau_min=1.0,
+                         gamma=0.5, D=8, steps=3) for k in range(2)]
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        oracles, gpus = [], []
+        for (p, tokens, masked, seq) in cases:
+            jp = J.JotParams(B=p.B, L=p.L, V=p.V, dtype=p.dtype, conf_mode=p.conf_mode, tau_max=p.tau_max,
+                             tau_min=p.tau_min, gamma=p.gamma, D=p.D, eps=p.eps, gen_start=p.gen_start,
+                             block_size=p.block_size)
+            oracles.append(O.OracleState.init(p, tokens, masked))
+            gpus.append(gpu.GpuJot(jp, tokens, masked))
+            assert gpus[-1].stream == side.cuda_stream
+        for n in range(3):
+            devs = []
+            for k, (p, tokens, masked, seq) in enumerate(cases):
+                lg = np.array(seq[n], np.float32)
+                clear_guard_band(oracles[k], lg)
+                devs.append(to_device(lg, p.dtype, p.V + (-p.V) % 4))
+                act = oracles[k].active_list()
+                oracles[k].step(as_rows(lg.reshape(p.B * p.L, p.V)[act], p.dtype))
+            for k in (0, 1):                                   # both enqueued before either is read
+                sl = devs[k].stride(1)
+                gpus[k].step(devs[k], stride_b=cases[k][0].L * sl, stride_l=sl)
+            for k in (1, 0):
+                np.testing.assert_array_equal(gpus[k].tokens(), oracles[k].tokens)
+                np.testing.assert_array_equal(gpus[k].active_list(), oracles[k].active_list().astype(np.int32))
+        for g in gpus:
+            g.close()
