@@ -154,8 +154,8 @@ def main():
                     help="only run the plain 1 GiB copy kernel N times (counter calibration) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only (the pass shards over batch rows with no "
-              "exchange; no multi-GPU figure is produced). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: one GPU only (the pass would shard over batch rows with no exchange; "
+              "no multi-GPU figure is produced). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -18,7 +18,7 @@ Followed passages of the paper (Section 4.1 and Algorithm 1):
                                  semi-autoregressive decoding only the current block is
                                  examined; finalization is uncapped.
 
-Readings where the paper is silent (all listed in the design document):
+Readings taken where the paper is silent:
 the argmax takes the smallest index among equal logits; p2 is the second entry
 of the sorted multiset (a duplicated maximum gives p2 = p1); positions outside
 the canvas contribute nothing to Eq. 3; d = 0 is excluded (i itself is masked);
