@@ -78,3 +78,22 @@ def test_sub_batch_equals_full_batch_rows():
     if full.n_bumps == 0 and sub.n_bumps == 0:      # overrides are inputs; equal only when none were needed
         np.testing.assert_array_equal(full.state.tokens[2], sub.state.tokens[0])
         np.testing.assert_array_equal(full.state.masked[2], sub.state.masked[0])
+
+
+def test_config1_matches_the_stored_oracle_results(golden_dir):
+    """Guards the input recipe and the oracle against accidental drift: the stored file was
+    written by tests/golden/write_config1_expected.py (generator + oracle only)."""
+    import json
+    import os
+    stored = json.load(open(os.path.join(golden_dir, "config1_expected.json")))
+    for name, mode, tau_max, tau_min in (("maxprob", CONF_MAXPROB, 0.9, 0.0), ("ratio", CONF_RATIO, 90.0, 1.0),
+                                         ("probgap", CONF_PROBGAP, 0.9, 0.0)):
+        cfg = CONFIGS[1].replace(conf_mode=mode, tau_max=tau_max, tau_min=tau_min)
+        rec, _, _, _ = LockstepRun(cfg, threads=2).next_step()
+        want = stored[name]
+        assert rec.active.tolist() == want["active"] and rec.token.tolist() == want["token"]
+        assert rec.commit.astype(int).tolist() == want["commit"]
+        for key in ("p1", "conf", "tau"):
+            got = getattr(rec, key)
+            ref = np.array([float.fromhex(h) for h in want[key]])
+            np.testing.assert_allclose(got, ref, rtol=1e-13, atol=0)
