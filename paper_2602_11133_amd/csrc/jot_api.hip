@@ -12,6 +12,7 @@
 #include "jot_compact.h"
 #include "jot_decide.h"
 #include "jot_device.h"
+#include "jot_row_step.h"
 #include "jot_sample.h"
 #include "jot_schedule.h"
 #include "jot_vocab_reduce.h"
@@ -28,10 +29,11 @@ constexpr int kDefaultWgPerCu = 4;
 constexpr int kMaxWgPerCu = 16;
 constexpr int kFallbackCus = 256;
 constexpr int kItemsPerWg = 4;
+constexpr int kPerRowStepMax = 2048;   // longest per-row examined list handled by the one-launch row kernel
 
 struct Layout {
     int64_t tokens, masked, commit_step, resolved_bits, active0, active1, counters, anomalies,
-        partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, last_m1, last_final, sample_list, sample_count, row_block, row_n_active,
+        partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, last_m1, last_final, sample_list, sample_count, row_block, row_n_active0, row_n_active1,
         row_n_commit, commit_log, total;
     int64_t n_partials;
     int32_t words_per_row;
@@ -84,7 +86,8 @@ Layout make_layout(const jot_params* p, int target_items)
     l.sample_list = take(n * 4);
     l.sample_count = take(4);
     l.row_block = take((int64_t)p->B * 4);
-    l.row_n_active = take((int64_t)p->B * 4);
+    l.row_n_active0 = take((int64_t)p->B * 4);
+    l.row_n_active1 = take((int64_t)p->B * 4);
     l.row_n_commit = take((int64_t)p->B * 4);
     l.commit_log = take(n * 12);
     l.total = off;
@@ -110,6 +113,7 @@ struct jot_state {
     HostCounters* host_dev;     // the device-side address of the same block
     hipEvent_t done;
     bool have_done;
+    bool per_row_step;          // decision + schedule + row counts in one per-row launch
     bool profile;
     hipEvent_t prof0[JOT_PROFILE_RING], prof1[JOT_PROFILE_RING];
     int32_t prof_step[JOT_PROFILE_RING];    // step recorded in each ring slot, 0 = none
@@ -117,21 +121,27 @@ struct jot_state {
     template <class T> T* at(int64_t off) const { return reinterpret_cast<T*>(ws + off); }
     int32_t* active(int which) const { return at<int32_t>(which ? lay.active1 : lay.active0); }
     JotCounters* counters(int which) const { return at<JotCounters>(lay.counters) + which; }
+    // per-row examined counts, double buffered like the counters: [cur] describes the list the
+    // next step reads, [cur ^ 1] is written by that step
+    int32_t* row_counts(int which) const { return at<int32_t>(which ? lay.row_n_active1 : lay.row_n_active0); }
 };
 
 namespace {
 
-int enqueue_compaction(jot_state* s, int32_t step, hipStream_t st)
+// Second half of the compaction (and, if `count_rows`, the first half too): ordered writes of the
+// next examined list, the commit log, the mask and its bit image, and the counters.
+int enqueue_compaction(jot_state* s, int32_t step, hipStream_t st, bool count_rows)
 {
     const int in = s->cur, out = s->cur ^ 1;
-    hipLaunchKernelGGL(jot_row_count_kernel, dim3(s->p.B), dim3(JOT_WG), 0, st, s->compact, step,
-                       s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
-                       s->at<int32_t>(s->lay.row_block), s->at<int32_t>(s->lay.row_n_active),
-                       s->at<int32_t>(s->lay.row_n_commit));
+    if (count_rows)
+        hipLaunchKernelGGL(jot_row_count_kernel, dim3(s->p.B), dim3(JOT_WG), 0, st, s->compact, step,
+                           s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
+                           s->at<int32_t>(s->lay.row_block), s->row_counts(out),
+                           s->at<int32_t>(s->lay.row_n_commit));
     hipLaunchKernelGGL(jot_row_write_kernel, dim3(s->p.B), dim3(JOT_WG), 0, st, s->compact, step,
                        s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
                        s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.row_block),
-                       s->at<int32_t>(s->lay.row_n_active), s->at<int32_t>(s->lay.row_n_commit),
+                       s->row_counts(out), s->at<int32_t>(s->lay.row_n_commit),
                        s->counters(in), s->counters(out), s->active(out),
                        s->at<int32_t>(s->lay.commit_log), s->at<uint64_t>(s->lay.resolved_bits),
                        s->at<unsigned long long>(s->lay.anomalies), s->host_dev,
@@ -204,6 +214,10 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
     s->lay = make_layout(p, max_target_items());
     s->cur = 0;
     s->step = 0;
+    {   // rows examine at most this many positions per step
+        const int per_row = (p->block_size > 0 && p->block_size < p->L) ? p->block_size : p->L;
+        s->per_row_step = per_row <= kPerRowStepMax;
+    }
     s->have_done = false;
     s->profile = false;
     s->host = nullptr;
@@ -249,7 +263,7 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
                        n, tokens_dev, masked_dev, s->at<int32_t>(s->lay.tokens),
                        s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
                        s->counters(0), s->at<unsigned long long>(s->lay.anomalies));
-    int rc2 = (hipGetLastError() == hipSuccess) ? enqueue_compaction(s, /*step=*/-1, st) : JOT_ERR_HIP;
+    int rc2 = (hipGetLastError() == hipSuccess) ? enqueue_compaction(s, /*step=*/-1, st, true) : JOT_ERR_HIP;
     if (rc2 == JOT_OK && hipStreamSynchronize(st) != hipSuccess) rc2 = JOT_ERR_HIP;
     if (rc2 != JOT_OK) {
         jot_release(s);
@@ -311,29 +325,53 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
         s->prof_step[slot] = step;
     }
 
-    hipLaunchKernelGGL(jot_decide_kernel, dim3((unsigned)((n + JOT_WG - 1) / JOT_WG)), dim3(JOT_WG), 0, st,
-                       s->decide, step, s->active(in), s->counters(in), s->at<JotPartial>(s->lay.partials),
-                       s->at<uint64_t>(s->lay.resolved_bits), s->at<int32_t>(s->lay.tokens),
-                       s->at<int32_t>(s->lay.commit_step), s->at<int32_t>(s->lay.last_token),
-                       s->at<float>(s->lay.last_conf), s->at<float>(s->lay.last_p1),
-                       s->at<float>(s->lay.last_p2), s->at<float>(s->lay.last_tau),
-                       s->at<uint8_t>(s->lay.last_flags), s->at<float>(s->lay.last_m1),
-                       s->at<int32_t>(s->lay.last_final),
-                       uniforms_dev ? s->at<int32_t>(s->lay.sample_list) : nullptr,
-                       s->at<int32_t>(s->lay.sample_count),
-                       s->at<unsigned long long>(s->lay.anomalies));
-    if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
-    if (n_transfer_dev || transfer_frac > 0.0f) {
-        JotScheduleParams sp;
-        sp.B = p.B; sp.L = p.L; sp.transfer_frac = transfer_frac;
-        hipLaunchKernelGGL(jot_schedule_kernel, dim3(p.B), dim3(JOT_WG), 0, st, sp, step, n_transfer_dev,
-                           s->active(in), s->at<int32_t>(s->lay.row_n_active), s->at<float>(s->lay.last_p1),
-                           s->at<float>(s->lay.last_conf), s->at<int32_t>(s->lay.last_token),
-                           s->at<uint8_t>(s->lay.last_flags), s->at<int32_t>(s->lay.tokens),
-                           s->at<int32_t>(s->lay.commit_step),
-                           uniforms_dev ? s->at<int32_t>(s->lay.sample_list) : nullptr,
-                           s->at<int32_t>(s->lay.sample_count));
+    JotDecideIO dio;
+    dio.active = s->active(in);
+    dio.partials = s->at<JotPartial>(s->lay.partials);
+    dio.resolved_bits = s->at<uint64_t>(s->lay.resolved_bits);
+    dio.tokens = s->at<int32_t>(s->lay.tokens);
+    dio.commit_step = s->at<int32_t>(s->lay.commit_step);
+    dio.last_token = s->at<int32_t>(s->lay.last_token);
+    dio.last_conf = s->at<float>(s->lay.last_conf);
+    dio.last_p1 = s->at<float>(s->lay.last_p1);
+    dio.last_p2 = s->at<float>(s->lay.last_p2);
+    dio.last_tau = s->at<float>(s->lay.last_tau);
+    dio.last_flags = s->at<uint8_t>(s->lay.last_flags);
+    dio.last_m1 = s->at<float>(s->lay.last_m1);
+    dio.last_final = s->at<int32_t>(s->lay.last_final);
+    dio.sample_list = uniforms_dev ? s->at<int32_t>(s->lay.sample_list) : nullptr;
+    dio.sample_count = s->at<int32_t>(s->lay.sample_count);
+    dio.anomalies = s->at<unsigned long long>(s->lay.anomalies);
+    const bool do_schedule = n_transfer_dev || transfer_frac > 0.0f;
+    JotScheduleParams sprm;
+    sprm.B = p.B; sprm.L = p.L; sprm.transfer_frac = transfer_frac;
+    JotScheduleIO sio;
+    sio.n_transfer = n_transfer_dev;
+    sio.active = dio.active;
+    sio.last_p1 = dio.last_p1;
+    sio.last_conf = dio.last_conf;
+    sio.last_token = dio.last_token;
+    sio.last_flags = dio.last_flags;
+    sio.tokens = dio.tokens;
+    sio.commit_step = dio.commit_step;
+    sio.sample_list = dio.sample_list;
+    sio.sample_count = dio.sample_count;
+
+    if (s->per_row_step) {
+        hipLaunchKernelGGL(jot_row_step_kernel, dim3(p.B), dim3(JOT_WG), 0, st, s->decide, dio, sprm, sio,
+                           do_schedule ? 1 : 0, s->compact, step, s->counters(in), s->at<uint8_t>(s->lay.masked),
+                           s->row_counts(in), s->at<int32_t>(s->lay.row_block), s->row_counts(in ^ 1),
+                           s->at<int32_t>(s->lay.row_n_commit));
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
+    } else {
+        hipLaunchKernelGGL(jot_decide_kernel, dim3((unsigned)((n + JOT_WG - 1) / JOT_WG)), dim3(JOT_WG), 0, st,
+                           s->decide, dio, step, s->counters(in));
+        if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
+        if (do_schedule) {
+            hipLaunchKernelGGL(jot_schedule_kernel, dim3(p.B), dim3(JOT_WG), 0, st, sprm, sio, step,
+                               s->row_counts(in));
+            if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
+        }
     }
     if (uniforms_dev) {
         const int grid = s->grid_sample;
@@ -350,7 +388,7 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     }
     s->step = step;
-    return enqueue_compaction(s, step, st);
+    return enqueue_compaction(s, step, st, /*count_rows=*/!s->per_row_step);
 }
 
 int64_t jot_active_count(jot_state* s)

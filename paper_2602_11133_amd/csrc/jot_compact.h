@@ -53,13 +53,13 @@ __device__ __forceinline__ int jot_block_reduce_sum(int v, int* lds)
 }
 
 // Pass 1: per batch row, the block currently being decoded and the two counts.
-__global__ __launch_bounds__(JOT_WG) void jot_row_count_kernel(
-    JotCompactParams prm, int32_t step, const uint8_t* __restrict__ masked,
-    const int32_t* __restrict__ commit_step, int32_t* __restrict__ row_block,
-    int32_t* __restrict__ row_n_active, int32_t* __restrict__ row_n_commit)
+// Called by every thread of the workgroup that owns row b (contains barriers); lds: JOT_WAVES ints.
+__device__ __forceinline__ void jot_row_count(const JotCompactParams& prm, int32_t step, int b,
+                                              const uint8_t* __restrict__ masked,
+                                              const int32_t* __restrict__ commit_step,
+                                              int32_t* __restrict__ row_block, int32_t* __restrict__ row_n_active,
+                                              int32_t* __restrict__ row_n_commit, int* lds)
 {
-    __shared__ int lds[JOT_WAVES];
-    const int b = blockIdx.x;
     const int64_t base = (int64_t)b * prm.L;
     int first = 0x7fffffff;
     for (int i = threadIdx.x; i < prm.L; i += JOT_WG) {
@@ -87,6 +87,15 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_count_kernel(
         row_n_active[b] = n_act;
         row_n_commit[b] = n_com;
     }
+}
+
+__global__ __launch_bounds__(JOT_WG) void jot_row_count_kernel(
+    JotCompactParams prm, int32_t step, const uint8_t* __restrict__ masked,
+    const int32_t* __restrict__ commit_step, int32_t* __restrict__ row_block,
+    int32_t* __restrict__ row_n_active, int32_t* __restrict__ row_n_commit)
+{
+    __shared__ int lds[JOT_WAVES];
+    jot_row_count(prm, step, blockIdx.x, masked, commit_step, row_block, row_n_active, row_n_commit, lds);
 }
 
 // Pass 2: exclusive prefix over rows, then ordered writes.

@@ -8,6 +8,26 @@
 #pragma once
 #include "jot_device.h"
 
+// Arrays the decision writes or reads, all in the caller's workspace.
+struct JotDecideIO {
+    const int32_t* active;
+    const JotPartial* partials;
+    const uint64_t* resolved_bits;
+    int32_t* tokens;
+    int32_t* commit_step;
+    int32_t* last_token;
+    float* last_conf;
+    float* last_p1;
+    float* last_p2;
+    float* last_tau;
+    uint8_t* last_flags;
+    float* last_m1;
+    int32_t* last_final;
+    int32_t* sample_list;       // NULL unless this step samples its tokens
+    int32_t* sample_count;
+    unsigned long long* anomalies;
+};
+
 struct JotDecideParams {
     int32_t L, V;
     int32_t conf_mode;
@@ -20,28 +40,15 @@ struct JotDecideParams {
     float gpow[JOT_MAX_D + 1];    // gpow[d] = gamma^d
 };
 
-__global__ __launch_bounds__(JOT_WG) void jot_decide_kernel(
-    JotDecideParams prm, int32_t step,
-    const int32_t* __restrict__ active, const JotCounters* __restrict__ counters,
-    const JotPartial* __restrict__ partials, const uint64_t* __restrict__ resolved_bits,
-    int32_t* __restrict__ tokens, int32_t* __restrict__ commit_step,
-    int32_t* __restrict__ last_token, float* __restrict__ last_conf, float* __restrict__ last_p1,
-    float* __restrict__ last_p2, float* __restrict__ last_tau, uint8_t* __restrict__ last_flags,
-    float* __restrict__ last_m1, int32_t* __restrict__ last_final,
-    int32_t* __restrict__ sample_list, int32_t* __restrict__ sample_count,   // NULL unless sampling
-    unsigned long long* __restrict__ anomalies)
+// Everything for one examined entry r of the list (pieces = pieces per row this step).
+__device__ __forceinline__ void jot_decide_one(const JotDecideParams& prm, const JotDecideIO& io,
+                                               int32_t step, int64_t r, int pieces)
 {
-    const int64_t n_active = counters->n_active;
-    const int64_t r = (int64_t)blockIdx.x * JOT_WG + threadIdx.x;
-    if (r >= n_active)
-        return;
-    const JotSplit sp = jot_plan_split(n_active, prm.V, prm.target_items, prm.split_align);
-
     // ---- merge the pieces of the row, in piece order
-    const JotPartial* q = partials + r * sp.S;
+    const JotPartial* q = io.partials + r * pieces;
     float m1 = q[0].m1, m2 = q[0].m2, M = q[0].M, s = q[0].s;
     int32_t idx = q[0].idx;
-    for (int j = 1; j < sp.S; ++j)
+    for (int j = 1; j < pieces; ++j)
         jot_merge(m1, idx, m2, M, s, q[j].m1, q[j].idx, q[j].m2, q[j].M, q[j].s);
 
     if (m1 == -INFINITY)
@@ -61,12 +68,12 @@ __global__ __launch_bounds__(JOT_WG) void jot_decide_kernel(
         conf = p1 - p2;
 
     // ---- Eq. 3: neighbours at distance d = 1..D on both sides, from the bit image
-    const int pos = active[r];
+    const int pos = io.active[r];
     const int b = pos / prm.L;
     const int i = pos - b * prm.L;
     float phi = 0.0f;
     if (prm.D > 0) {
-        const uint64_t* words = resolved_bits + (int64_t)b * prm.words_per_row;
+        const uint64_t* words = io.resolved_bits + (int64_t)b * prm.words_per_row;
         const int wi = i >> 6, bi = i & 63;
         const uint64_t mid = words[wi];
         const uint64_t lo = wi > 0 ? words[wi - 1] : 0ull;
@@ -86,19 +93,31 @@ __global__ __launch_bounds__(JOT_WG) void jot_decide_kernel(
 
     const bool commit = has_softmax && (conf >= tau);           // Eq. 6
     if (commit) {
-        tokens[pos] = idx;
-        commit_step[pos] = step;
-        if (sample_list)        // unordered work list for the sampling kernel (rows are independent)
-            sample_list[atomicAdd(sample_count, 1)] = (int32_t)r;
+        io.tokens[pos] = idx;
+        io.commit_step[pos] = step;
+        if (io.sample_list)        // unordered work list for the sampling kernel (rows are independent)
+            io.sample_list[atomicAdd(io.sample_count, 1)] = (int32_t)r;
     }
     if (!has_softmax)
-        atomicAdd(anomalies, 1ull);
-    last_token[r] = idx;
-    last_final[r] = idx;            // the sampling kernel, if it runs, overwrites this
-    last_m1[r] = m1;
-    last_flags[r] = commit ? 1 : 0;
-    last_conf[r] = has_softmax ? conf : __uint_as_float(0x7fc00000u);
-    last_p1[r] = p1;
-    last_p2[r] = p2;
-    last_tau[r] = tau;
+        atomicAdd(io.anomalies, 1ull);
+    io.last_token[r] = idx;
+    io.last_final[r] = idx;            // the sampling kernel, if it runs, overwrites this
+    io.last_m1[r] = m1;
+    io.last_flags[r] = commit ? 1 : 0;
+    io.last_conf[r] = has_softmax ? conf : __uint_as_float(0x7fc00000u);
+    io.last_p1[r] = p1;
+    io.last_p2[r] = p2;
+    io.last_tau[r] = tau;
+}
+
+// One thread per examined position (used when rows are too long for the per-row kernel).
+__global__ __launch_bounds__(JOT_WG) void jot_decide_kernel(JotDecideParams prm, JotDecideIO io, int32_t step,
+                                                            const JotCounters* __restrict__ counters)
+{
+    const int64_t n_active = counters->n_active;
+    const int64_t r = (int64_t)blockIdx.x * JOT_WG + threadIdx.x;
+    if (r >= n_active)
+        return;
+    const JotSplit sp = jot_plan_split(n_active, prm.V, prm.target_items, prm.split_align);
+    jot_decide_one(prm, io, step, r, sp.S);
 }

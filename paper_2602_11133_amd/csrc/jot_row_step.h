@@ -1,0 +1,35 @@
+// Per-row step kernel: for canvases whose rows examine at most a couple of thousand positions
+// per step (every workload of the paper's shape) the decision (Eq. 2 - Eq. 6), the optional
+// transfer schedule and the per-row counting pass of the compaction run in ONE launch, one
+// workgroup per batch row, instead of three.  Nothing crosses rows here: a row's slice of the
+// examined list is found from the per-row counts of the previous step, and the counts for the
+// next step go to the other half of a double buffer (a workgroup that starts late must still
+// see the old counts of the rows before it).
+#pragma once
+#include "jot_compact.h"
+#include "jot_decide.h"
+#include "jot_schedule.h"
+
+__global__ __launch_bounds__(JOT_WG) void jot_row_step_kernel(
+    JotDecideParams dprm, JotDecideIO dio, JotScheduleParams sprm, JotScheduleIO sio, int do_schedule,
+    JotCompactParams cprm, int32_t step, const JotCounters* __restrict__ counters,
+    const uint8_t* __restrict__ masked, const int32_t* __restrict__ row_n_active_in,
+    int32_t* __restrict__ row_block, int32_t* __restrict__ row_n_active_out,
+    int32_t* __restrict__ row_n_commit)
+{
+    __shared__ int lds[JOT_WAVES];
+    __shared__ int wave_eq[JOT_WAVES];
+    const int b = blockIdx.x;
+    const int64_t base = jot_row_base(row_n_active_in, b, lds);
+    const int n = row_n_active_in[b];
+    const JotSplit sp = jot_plan_split(counters->n_active, dprm.V, dprm.target_items, dprm.split_align);
+
+    for (int j = threadIdx.x; j < n; j += JOT_WG)
+        jot_decide_one(dprm, dio, step, base + j, sp.S);
+    __syncthreads();                       // this row's results are visible to the whole workgroup
+    if (do_schedule) {
+        jot_schedule_row(sprm, sio, step, b, base, n, lds, wave_eq);
+        __syncthreads();
+    }
+    jot_row_count(cprm, step, b, masked, dio.commit_step, row_block, row_n_active_out, row_n_commit, lds);
+}

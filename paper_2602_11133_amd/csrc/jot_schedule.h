@@ -30,33 +30,33 @@ __device__ __forceinline__ int jot_wg_sum(int v, int* lds)      // v already sum
     return r;
 }
 
-__global__ __launch_bounds__(JOT_WG) void jot_schedule_kernel(
-    JotScheduleParams prm, int32_t step, const int32_t* __restrict__ n_transfer,
-    const int32_t* __restrict__ active, const int32_t* __restrict__ row_n_active,
-    const float* __restrict__ last_p1, const float* __restrict__ last_conf,
-    const int32_t* __restrict__ last_token, uint8_t* __restrict__ last_flags,
-    int32_t* __restrict__ tokens, int32_t* __restrict__ commit_step,
-    int32_t* __restrict__ sample_list, int32_t* __restrict__ sample_count)   // NULL unless sampling
-{
-    __shared__ int lds[JOT_WAVES];
-    __shared__ int wave_eq[JOT_WAVES];
-    const int b = blockIdx.x;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+// Arrays of the schedule pass, all in the caller's workspace.
+struct JotScheduleIO {
+    const int32_t* n_transfer;      // [B] device, or NULL
+    const int32_t* active;
+    const float* last_p1;
+    const float* last_conf;
+    const int32_t* last_token;
+    uint8_t* last_flags;
+    int32_t* tokens;
+    int32_t* commit_step;
+    int32_t* sample_list;           // NULL unless this step samples its tokens
+    int32_t* sample_count;
+};
 
-    // this row's slice [base, base + n) of the examined list
-    int pa = 0;
-    for (int k = threadIdx.x; k < b; k += JOT_WG) pa += row_n_active[k];
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) pa += __shfl_xor(pa, off, 64);
-    const int64_t base = jot_wg_sum(pa, lds);
-    const int n = row_n_active[b];
+// The schedule of batch row b, whose examined entries are [base, base + n) of the list.
+// Called by every thread of the workgroup (it contains barriers); lds / wave_eq: JOT_WAVES ints each.
+__device__ __forceinline__ void jot_schedule_row(const JotScheduleParams& prm, const JotScheduleIO& io,
+                                                 int32_t step, int b, int64_t base, int n, int* lds, int* wave_eq)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (n == 0)
         return;
 
     // key of entry j: bit pattern of p1, or 0 for a row without a softmax (conf is NaN there)
     auto load_key = [&](int j) -> uint32_t {
-        const float c = last_conf[base + j];
-        return (c == c) ? __float_as_uint(last_p1[base + j]) : 0u;
+        const float c = io.last_conf[base + j];
+        return (c == c) ? __float_as_uint(io.last_p1[base + j]) : 0u;
     };
     // Rows of up to JOT_SCHED_CACHE * 256 examined positions keep their keys in registers
     // (thread t holds entries t, t + 256, ...); longer rows re-read them from memory each pass.
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_schedule_kernel(
 
     // how many to reveal
     const int n_valid = count_ge(1u);
-    long long want = (n_transfer ? (long long)n_transfer[b] : 0ll) +
+    long long want = (io.n_transfer ? (long long)io.n_transfer[b] : 0ll) +
                      (long long)floor((double)prm.transfer_frac * (double)n);
     if (want > n_valid) want = n_valid;
     if (want <= 0)
@@ -135,16 +135,37 @@ __global__ __launch_bounds__(JOT_WG) void jot_schedule_kernel(
         const bool take = above || (equal && off + __popcll(m_eq & below) < need_eq);
         if (take) {
             const int64_t r = base + j;
-            const int pos = active[r];
-            last_flags[r] |= 2;
-            if (commit_step[pos] != step) {          // not already finalized by the early exit
-                tokens[pos] = last_token[r];
-                commit_step[pos] = step;
-                if (sample_list)
-                    sample_list[atomicAdd(sample_count, 1)] = (int32_t)r;
+            const int pos = io.active[r];
+            io.last_flags[r] |= 2;
+            if (io.commit_step[pos] != step) {          // not already finalized by the early exit
+                io.tokens[pos] = io.last_token[r];
+                io.commit_step[pos] = step;
+                if (io.sample_list)
+                    io.sample_list[atomicAdd(io.sample_count, 1)] = (int32_t)r;
             }
         }
         run_eq += tot;
         __syncthreads();
     }
+}
+
+// Sum over the batch rows before b of the per-row examined counts = start of row b's slice.
+__device__ __forceinline__ int64_t jot_row_base(const int32_t* __restrict__ row_n_active, int b, int* lds)
+{
+    int pa = 0;
+    for (int k = threadIdx.x; k < b; k += JOT_WG) pa += row_n_active[k];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) pa += __shfl_xor(pa, off, 64);
+    return jot_wg_sum(pa, lds);
+}
+
+// Stand-alone launch (used when rows are too long for the per-row kernel): one workgroup per row.
+__global__ __launch_bounds__(JOT_WG) void jot_schedule_kernel(JotScheduleParams prm, JotScheduleIO io, int32_t step,
+                                                              const int32_t* __restrict__ row_n_active)
+{
+    __shared__ int lds[JOT_WAVES];
+    __shared__ int wave_eq[JOT_WAVES];
+    const int b = blockIdx.x;
+    const int64_t base = jot_row_base(row_n_active, b, lds);
+    jot_schedule_row(prm, io, step, b, base, row_n_active[b], lds, wave_eq);
 }
