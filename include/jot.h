@@ -104,8 +104,10 @@ int jot_init_state(jot_state** out, const jot_params* p,
  *                Must be 16-byte aligned, and stride_b, stride_l must keep every row 16-byte
  *                aligned.  Read-only; only rows of examined positions are touched, so rows of
  *                frozen positions need not hold valid data.
- *   -inf logits are allowed (probability 0).  A row holding NaN or +inf, or only -inf, has no
- *   softmax: the position is left masked and counted by jot_anomaly_count().
+ *   -inf logits are allowed (probability 0), and so are very negative finite fill values
+ *   (-1e9, -1e30, -FLT_MAX): they contribute 0.  A row holding NaN or +inf, or only -inf, or
+ *   whose largest logit lies outside [-4e6, 4e6], has no softmax here: the position is left
+ *   masked and counted by jot_anomaly_count().
  * Asynchronous: returns after enqueueing on `stream`.  With no examined position left it is a
  * no-op on the canvas (Algorithm 1 would have left the loop).
  */

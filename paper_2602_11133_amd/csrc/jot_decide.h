@@ -55,8 +55,10 @@ __device__ __forceinline__ void jot_decide_one(const JotDecideParams& prm, const
         idx = 0;            // every logit is -inf: all are equal, the smallest index is 0
 
     // ---- probabilities: S = sum_v exp(l_v - m1) = s * 2^(M - m1*log2 e); p1 = 1/S, p2 = e^(m2-m1)/S
-    const float S = s * exp2f(fmaf(-m1, JOT_LOG2E, M));
-    const bool has_softmax = (S >= 0.5f) && (S < INFINITY) && (m1 < INFINITY);   // false for NaN
+    const float S_raw = s * exp2f(fmaf(-m1, JOT_LOG2E, M));
+    const float S = fmaxf(S_raw, 1.0f);     // the maximum itself contributes exp(0) = 1: rounding may not go below
+    const bool has_softmax = (S_raw >= 0.5f) && (S_raw < INFINITY) &&           // false for NaN
+                             (m1 >= -JOT_LOGIT_LIMIT) && (m1 <= JOT_LOGIT_LIMIT);
     const float p1 = 1.0f / S;
     const float p2 = expf(m2 - m1) / S;
     float conf;

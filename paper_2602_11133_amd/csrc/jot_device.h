@@ -66,6 +66,14 @@ struct JotHostBlock {
 
 #define JOT_LOG2E 1.44269504088896340736f
 
+// Supported range of a row's LARGEST logit.  The exponent sums work in base 2 on l * log2(e);
+// that product is exact to better than one unit only while it stays below 2^23, i.e. for
+// |l| < 5.8e6.  A row whose maximum lies outside +-JOT_LOGIT_LIMIT is reported as having no
+// softmax (never finalized, counted as an anomaly).  Entries far BELOW the range (fill values
+// such as -1e9, -1e30, -FLT_MAX, -inf used to mask tokens) are fine: they contribute 0.
+#define JOT_LOGIT_LIMIT 4.0e6f
+#define JOT_EXPONENT_FLOOR (-8388608.0f)   // -2^23: lowest reference exponent a lane will take
+
 // Lexicographic merge of two pieces of the same row: larger logit first, then smaller index.
 // m2 is the second entry of the merged multiset; the sums are brought to the common reference.
 __device__ __forceinline__ void jot_merge(float& m1, int32_t& idx, float& m2, float& M, float& s,

@@ -89,7 +89,9 @@ __device__ __forceinline__ void jot_rereference(JotLane& a)
 {
     const float t = a.m1 * JOT_LOG2E;
     if (t > a.M + 32.0f) {
-        const float newM = ceilf(t);
+        // a lane that has only seen fill values (-1e9, -1e30 ...) parks its reference at the floor:
+        // their terms then underflow to exactly 0 instead of inheriting the rounding of a huge product
+        const float newM = ceilf(fmaxf(t, JOT_EXPONENT_FLOOR));
         const float f = (a.M == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(a.M - newM);
         a.s0 *= f; a.s1 *= f; a.s2 *= f; a.s3 *= f;
         a.M = newM;

@@ -86,3 +86,12 @@ def test_package_has_no_cpu_fallback():
     # the binding computes nothing: it must not import the oracle or numpy math paths for the method
     src = open(os.path.join(ROOT, "paper_2602_11133_amd", "binding.py")).read()
     assert "oracle" not in src
+
+
+def test_header_is_valid_c_and_cpp(tmp_path):
+    import subprocess
+    src = tmp_path / "use_jot.c"
+    src.write_text('#include "jot.h"\nint main(void) { jot_params p; p.B = 1; (void)p; return jot_workspace_bytes(0) < 0 ? 0 : 1; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc, str(src)])
+    subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)])

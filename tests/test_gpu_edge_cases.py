@@ -427,3 +427,52 @@ def test_two_states_interleaved_on_a_side_stream(gpu):
                 np.testing.assert_array_equal(gpus[k].active_list(), oracles[k].active_list().astype(np.int32))
         for g in gpus:
             g.close()
+
+
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+def test_adversarial_rows(gpu, dtype):
+    # rows built to stress the running reference of the exponent sums and the tie rules
+    V, L = 20_000, 12
+    p = O.OracleParams(B=1, L=L, V=V, dtype=dtype, conf_mode=O.CONF_RATIO, tau_max=3.0, tau_min=1.0, D=0)
+    v = np.arange(V, dtype=np.float32)
+    lg = np.zeros((1, L, V), np.float32)
+    lg[0, 0] = v * 0.5                                   # steady climb to 1e4: the reference moves many times
+    lg[0, 1] = -v * 0.5                                  # steady fall: maximum first
+    lg[0, 2] = np.where(v % 2 == 0, 1.0e4, -1.0e4)       # alternating extremes, tied maxima
+    lg[0, 3] = 3.0e6                                     # constant at the edge of the supported range
+    lg[0, 4] = np.where(v % 5 == 0, -3.0e6, -3.0e6 - 8)
+    lg[0, 5] = np.where(v == 777, 2.0, np.where(v > 9000, -1.0e30, -3.0e38))   # fill values around one real logit
+    lg[0, 6] = 1.0e-40                                   # subnormal in binary32
+    lg[0, 7] = np.where(v % 3 == 0, -0.0, 0.0)           # signed zeros are equal: lowest index wins
+    lg[0, 8] = np.sin(v) * 50.0                          # oscillating, several near-maxima
+    lg[0, 9] = np.minimum(v, 100.0)                      # long plateau of equal maxima from index 100
+    lg[0, 10] = np.where(v < V - 1, -np.inf, 3.0)        # one finite entry at the very end
+    lg[0, 11] = (v % 97) * 0.25 - 1.0e3                  # sawtooth far below zero
+    toks, msk, log, last = check_case(gpu, p, np.zeros((1, L), np.int32), np.ones((1, L), bool), [lg], clear=False)
+    assert last["token"][3] == 0 and last["token"][5] == 777 and last["token"][7] == 0
+    assert last["p1"][5] == 1.0 and last["p2"][5] == 0.0
+    assert last["token"][9] == 100 and last["token"][10] == V - 1
+    if dtype == O.F32:                                   # (in bf16 the top of the ramp is a plateau of equal values)
+        assert last["token"][0] == V - 1
+
+
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+def test_fill_values_and_out_of_range_maxima(gpu, dtype):
+    # masked-token fill values of any size count as probability 0; a row whose largest logit is
+    # outside [-4e6, 4e6] is outside the supported domain and is reported as having no softmax
+    import paper_2602_11133_amd as J
+    V, L = 70_000, 8
+    rng = np.random.default_rng(70)
+    p = O.OracleParams(B=1, L=L, V=V, dtype=dtype, conf_mode=O.CONF_MAXPROB, tau_max=0.0, tau_min=0.0, D=0)
+    lg = rng.standard_normal((1, L, V)).astype(np.float32)
+    lg[0, 0, 30_000:] = -1.0e9                           # a whole region masked with a finite fill value
+    lg[0, 1, :60_000] = -1.0e30
+    lg[0, 2, ::3] = -3.0e38
+    lg[0, 3, 10_000:50_000] = -np.inf
+    lg[0, 4, :] = 1.0e30                                 # out of range
+    lg[0, 5, 123] = 5.0e6                                # out of range maximum
+    lg[0, 6, :] = -1.0e9                                 # everything "masked": out of range
+    lg[0, 7, 5] = 3.9e6                                  # in range, far above the rest
+    toks, msk, log, last = check_case(gpu, p, np.zeros((1, L), np.int32), np.ones((1, L), bool), [lg], clear=False)
+    assert msk[0].tolist() == [False, False, False, False, True, True, True, False]
+    assert toks[0, 7] == 5 and toks[0, 0] < 30_000 and toks[0, 1] >= 60_000

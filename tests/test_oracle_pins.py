@@ -454,3 +454,16 @@ def test_simultaneous_update_within_a_step():
     rec2 = st.step_full(logits)
     assert rec2.tau.tolist() == [1.0] and rec2.commit.tolist() == [True]
     assert st.commit_log == [(1, 4, 2), (2, 5, 1)]
+
+
+def test_supported_range_of_the_row_maximum():
+    # library convention: the largest logit must lie in [-4e6, 4e6]; fill values below are fine
+    rows = np.zeros((5, 6), np.float32)
+    rows[0, :] = [-1e30, 1.0, -3e38, 0.0, -1e9, -np.inf]
+    rows[1, :] = 4.0e6
+    rows[2, :] = 4.1e6
+    rows[3, :] = -4.1e6
+    rows[4, :] = [3.9e6, -3.9e6, 0, 0, 0, 0]
+    a, m1, m2, S, st = O.row_stats(rows, O.F32)
+    assert st.tolist() == [0, 0, 1, 1, 0]
+    assert a[0] == 1 and abs(S[0] - (1 + math.exp(-1))) < 1e-15 and S[1] == 6.0 and S[4] == 1.0
