@@ -32,9 +32,9 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # workload 5: see profiles/vocab_reduce_cfg5_hbm_traffic.md.  Valid only for the kernel sources
 # with these hashes and for that workload; otherwise bench.py reports null.
 MEASURED_TRAFFIC = {
-    "config": 5, "steps": 4, "bytes_per_launch": (38559354 + 2027) * 1024,
-    "sha256": {"jot_vocab_reduce.h": "d3f49bd7d939c5cbef43f6f2c80c091647f851ecdc2700b7eca6862dff8408fc",
-               "jot_device.h": "0e38a0aea5ae16bfd5a6121aedfeb01de358c4ddc5246d750679baa6b6f6ee95"},
+    "config": 5, "steps": 4, "bytes_per_launch": (38558975 + 2027) * 1024,
+    "sha256": {"jot_vocab_reduce.h": "2b244449b0d5b1c615f73cf902a1430941e4692ab4fe78218ffd64f753825760",
+               "jot_device.h": "fdae872d300152b1e26e3c3c7c82bd89f03ac5634e217b88af4c3b7fd3868657"},
 }
 
 
