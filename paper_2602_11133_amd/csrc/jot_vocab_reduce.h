@@ -83,12 +83,15 @@ __device__ __forceinline__ void jot_top2(JotLane& a, const float (&x)[N], const 
     a.best_raw.w = better ? raw.w : a.best_raw.w;
 }
 
-// Keep every exponent l*log2(e) - M of the lane at or below 32: when the running maximum has
+// Keep every exponent l*log2(e) - M of the lane at or below 8: when the running maximum has
 // climbed past that, move the reference to it and rescale the sums (exact: M is an integer).
+// Small exponents keep the rounding of the FMA that forms them small (half an ulp of at most 8,
+// i.e. 5e-7) for the terms that matter; the branch is rare (the lane maximum of ordinary rows
+// settles within the first batch).
 __device__ __forceinline__ void jot_rereference(JotLane& a)
 {
     const float t = a.m1 * JOT_LOG2E;
-    if (t > a.M + 32.0f) {
+    if (t > a.M + 8.0f) {
         // a lane that has only seen fill values (-1e9, -1e30 ...) parks its reference at the floor:
         // their terms then underflow to exactly 0 instead of inheriting the rounding of a huge product
         const float newM = ceilf(fmaxf(t, JOT_EXPONENT_FLOOR));
