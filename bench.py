@@ -32,8 +32,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # workload 5: see profiles/vocab_reduce_cfg5_hbm_traffic.md.  Valid only for the kernel sources
 # with these hashes and for that workload; otherwise bench.py reports null.
 MEASURED_TRAFFIC = {
-    "config": 5, "steps": 4, "bytes_per_launch": (38558975 + 2027) * 1024,
-    "sha256": {"jot_vocab_reduce.h": "2b244449b0d5b1c615f73cf902a1430941e4692ab4fe78218ffd64f753825760",
+    "config": 5, "steps": 4, "bytes_per_launch": (38558961 + 2027) * 1024,
+    "sha256": {"jot_vocab_reduce.h": "d7b74f4290474b8456b96e31bb8012b97e69a315b8c606d3bda320f787276762",
                "jot_device.h": "fdae872d300152b1e26e3c3c7c82bd89f03ac5634e217b88af4c3b7fd3868657"},
 }
 
