@@ -28,6 +28,8 @@
  *     or the caller must order the streams itself.
  *   - Return value 0 = success, negative = one of JOT_ERR_*.  Arguments are validated on the
  *     host before any device work, so a failing call has no effect on the device.
+ *   - A state belongs to the HIP device that was current in jot_init_state(); later calls on it
+ *     must be made with the same device current (else JOT_ERR_WRONG_DEVICE).
  *   - Calls on the same state must not overlap (one thread at a time); different states are
  *     independent.
  *   - Indices: a canvas position is the flattened index b*L + i, 0 <= b < B, 0 <= i < L.
@@ -61,7 +63,9 @@ enum {
     JOT_ERR_WORKSPACE_TOO_SMALL = -4,
     JOT_ERR_MISALIGNED          = -5,
     JOT_ERR_HIP                 = -6,
-    JOT_ERR_NO_DEVICE           = -7
+    JOT_ERR_NO_DEVICE           = -7,
+    JOT_ERR_NO_MEMORY           = -8,   /* host allocation failed */
+    JOT_ERR_WRONG_DEVICE        = -9    /* the current HIP device is not the one the state was created on */
 };
 
 typedef struct {

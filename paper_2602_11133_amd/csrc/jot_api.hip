@@ -100,6 +100,7 @@ using HostCounters = JotHostBlock;
 
 struct jot_state {
     jot_params p;
+    int device;                 // HIP device the state lives on
     Layout lay;
     char* ws;
     int cur;                    // which counter block / active list the next step reads
@@ -192,8 +193,9 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
     if (cus > 2048) cus = 2048;
 
     jot_state* s = new (std::nothrow) jot_state();
-    if (!s) return JOT_ERR_INVALID_ARG;
+    if (!s) return JOT_ERR_NO_MEMORY;
     s->p = *p;
+    s->device = dev;
     s->ws = static_cast<char*>(workspace_dev);
     // persistent grid = exactly the workgroups that can be resident at once
     int occ = 0;
@@ -290,6 +292,9 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
 {
     if (!s || !logits_dev) return JOT_ERR_NULL_POINTER;
     if (reinterpret_cast<uintptr_t>(uniforms_dev) % 4) return JOT_ERR_MISALIGNED;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return JOT_ERR_NO_DEVICE;
+    if (dev != s->device) return JOT_ERR_WRONG_DEVICE;
     if (!(transfer_frac >= 0.0f && transfer_frac <= 1.0f)) return JOT_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(n_transfer_dev) % 4) return JOT_ERR_MISALIGNED;
     const jot_params& p = s->p;
@@ -483,6 +488,8 @@ const char* jot_strerror(int code)
     case JOT_ERR_MISALIGNED: return "misaligned pointer or stride";
     case JOT_ERR_HIP: return "HIP runtime error";
     case JOT_ERR_NO_DEVICE: return "no HIP device";
+    case JOT_ERR_NO_MEMORY: return "out of host memory";
+    case JOT_ERR_WRONG_DEVICE: return "state belongs to another HIP device";
     default: return "unknown error";
     }
 }
