@@ -168,7 +168,9 @@ int64_t jot_anomaly_count(jot_state* s);
 const int32_t* jot_tokens(const jot_state* s);        /* [B, L] current canvas                        */
 const uint8_t* jot_masked(const jot_state* s);        /* [B, L] 1 = still masked                      */
 const int32_t* jot_commit_step(const jot_state* s);   /* [B, L] step at which finalized, 0 = not (yet) */
-const int32_t* jot_active_list(const jot_state* s);   /* [jot_active_count] ascending b*L+i, next step */
+const int32_t* jot_active_list(jot_state* s);         /* [jot_active_count] ascending b*L+i, next step;
+                                                         waits like jot_active_count (the list is double
+                                                         buffered; which half is current is device state) */
 /* Finalizations in order: triples (step, b*L+i, token), steps non-decreasing, positions
  * ascending within a step.  *n receives the number of triples (waits like jot_active_count). */
 const int32_t* jot_commit_log(jot_state* s, int64_t* n);

@@ -32,7 +32,7 @@ constexpr int kItemsPerWg = 4;
 constexpr int kPerRowStepMax = 2048;   // longest per-row examined list handled by the one-launch row kernel
 
 struct Layout {
-    int64_t tokens, masked, commit_step, resolved_bits, active0, active1, counters, anomalies,
+    int64_t tokens, masked, commit_step, resolved_bits, active0, active1, counters, epoch, anomalies,
         partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, last_m1, last_final, sample_list, sample_count, row_block, row_n_active0, row_n_active1,
         row_n_commit, commit_log, total;
     int64_t n_partials;
@@ -73,6 +73,7 @@ Layout make_layout(const jot_params* p, int target_items)
     l.active0 = take(n * 4);
     l.active1 = take(n * 4);
     l.counters = take(2 * sizeof(JotCounters));
+    l.epoch = take(sizeof(JotEpoch));
     l.anomalies = take(8);
     l.partials = take(l.n_partials * (int64_t)sizeof(JotPartial));
     l.last_token = take(n * 4);
@@ -103,7 +104,8 @@ struct jot_state {
     int device;                 // HIP device the state lives on
     Layout lay;
     char* ws;
-    int cur;                    // which counter block / active list the next step reads
+    JotFrame frame;             // device pointers of the double buffers and the epoch
+    bool sync_device;           // the last step was enqueued under stream capture: wait = device sync
     int32_t step;
     int grid_reduce;
     int grid_sample;
@@ -122,43 +124,58 @@ struct jot_state {
     template <class T> T* at(int64_t off) const { return reinterpret_cast<T*>(ws + off); }
     int32_t* active(int which) const { return at<int32_t>(which ? lay.active1 : lay.active0); }
     JotCounters* counters(int which) const { return at<JotCounters>(lay.counters) + which; }
-    // per-row examined counts, double buffered like the counters: [cur] describes the list the
-    // next step reads, [cur ^ 1] is written by that step
     int32_t* row_counts(int which) const { return at<int32_t>(which ? lay.row_n_active1 : lay.row_n_active0); }
 };
 
 namespace {
 
-// Second half of the compaction (and, if `count_rows`, the first half too): ordered writes of the
-// next examined list, the commit log, the mask and its bit image, and the counters.
-int enqueue_compaction(jot_state* s, int32_t step, hipStream_t st, bool count_rows)
+bool stream_is_capturing(hipStream_t st)
 {
-    const int in = s->cur, out = s->cur ^ 1;
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &status) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return status != hipStreamCaptureStatusNone;
+}
+
+// Second half of the compaction (and, if `count_rows`, the first half too): ordered writes of the
+// next examined list, the commit log, the mask and its bit image, the counters; its last
+// workgroup closes the step (flips the double buffers in the device-side epoch).
+int enqueue_compaction(jot_state* s, bool creating, hipStream_t st, bool count_rows)
+{
     if (count_rows)
-        hipLaunchKernelGGL(jot_row_count_kernel, dim3(s->p.B), dim3(JOT_WG), 0, st, s->compact, step,
-                           s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
-                           s->at<int32_t>(s->lay.row_block), s->row_counts(out),
-                           s->at<int32_t>(s->lay.row_n_commit));
-    hipLaunchKernelGGL(jot_row_write_kernel, dim3(s->p.B), dim3(JOT_WG), 0, st, s->compact, step,
-                       s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
+        hipLaunchKernelGGL(jot_row_count_kernel, dim3(s->p.B), dim3(JOT_WG), 0, st, s->compact, s->frame,
+                           creating ? 1 : 0, s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
+                           s->at<int32_t>(s->lay.row_block), s->at<int32_t>(s->lay.row_n_commit));
+    hipLaunchKernelGGL(jot_row_write_kernel, dim3(s->p.B), dim3(JOT_WG), 0, st, s->compact, s->frame,
+                       creating ? 1 : 0, s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
                        s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.row_block),
-                       s->row_counts(out), s->at<int32_t>(s->lay.row_n_commit),
-                       s->counters(in), s->counters(out), s->active(out),
-                       s->at<int32_t>(s->lay.commit_log), s->at<uint64_t>(s->lay.resolved_bits),
-                       s->at<unsigned long long>(s->lay.anomalies), s->host_dev,
-                       s->at<int32_t>(s->lay.sample_count));
+                       s->at<int32_t>(s->lay.row_n_commit), s->at<int32_t>(s->lay.commit_log),
+                       s->at<uint64_t>(s->lay.resolved_bits), s->at<unsigned long long>(s->lay.anomalies),
+                       s->host_dev, s->at<int32_t>(s->lay.sample_count));
     if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
-    // the kernel above also wrote the new counters into pinned host memory; the host waits on this
-    if (hipEventRecord(s->done, st) != hipSuccess) return JOT_ERR_HIP;
-    s->have_done = true;
-    s->cur = out;
+    // The kernel above also wrote the new counters into pinned host memory.  Outside stream
+    // capture the host waits on an event recorded here; a captured step may be replayed any number
+    // of times later, so after one the host waits for the whole device instead.
+    if (stream_is_capturing(st)) {
+        s->sync_device = true;
+    } else {
+        if (hipEventRecord(s->done, st) != hipSuccess) return JOT_ERR_HIP;
+        s->have_done = true;
+        s->sync_device = false;
+    }
     return JOT_OK;
 }
 
 int wait_done(jot_state* s)
 {
     if (!s) return JOT_ERR_NULL_POINTER;
-    if (s->have_done && hipEventSynchronize(s->done) != hipSuccess) return JOT_ERR_HIP;
+    if (s->sync_device) {
+        if (hipDeviceSynchronize() != hipSuccess) return JOT_ERR_HIP;
+    } else if (s->have_done && hipEventSynchronize(s->done) != hipSuccess) {
+        return JOT_ERR_HIP;
+    }
     return JOT_OK;
 }
 
@@ -214,8 +231,14 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
     s->target_items = s->grid_reduce * kItemsPerWg;
     if (s->target_items > max_target_items()) s->target_items = max_target_items();
     s->lay = make_layout(p, max_target_items());
-    s->cur = 0;
     s->step = 0;
+    s->sync_device = false;
+    s->frame.epoch = s->at<JotEpoch>(s->lay.epoch);
+    for (int h = 0; h < 2; ++h) {
+        s->frame.active[h] = s->active(h);
+        s->frame.counters[h] = s->counters(h);
+        s->frame.row_counts[h] = s->row_counts(h);
+    }
     {   // rows examine at most this many positions per step
         const int per_row = (p->block_size > 0 && p->block_size < p->L) ? p->block_size : p->L;
         s->per_row_step = per_row <= kPerRowStepMax;
@@ -264,8 +287,8 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
     hipLaunchKernelGGL(jot_init_copy_kernel, dim3((unsigned)((n + JOT_WG - 1) / JOT_WG)), dim3(JOT_WG), 0, st,
                        n, tokens_dev, masked_dev, s->at<int32_t>(s->lay.tokens),
                        s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
-                       s->counters(0), s->at<unsigned long long>(s->lay.anomalies));
-    int rc2 = (hipGetLastError() == hipSuccess) ? enqueue_compaction(s, /*step=*/-1, st, true) : JOT_ERR_HIP;
+                       s->counters(0), s->at<unsigned long long>(s->lay.anomalies), s->frame.epoch);
+    int rc2 = (hipGetLastError() == hipSuccess) ? enqueue_compaction(s, /*creating=*/true, st, true) : JOT_ERR_HIP;
     if (rc2 == JOT_OK && hipStreamSynchronize(st) != hipSuccess) rc2 = JOT_ERR_HIP;
     if (rc2 != JOT_OK) {
         jot_release(s);
@@ -307,31 +330,31 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
         return JOT_ERR_MISALIGNED;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int32_t step = s->step + 1;
-    const int in = s->cur;
+    const int32_t step = s->step + 1;           // host-side call count; the kernels use the device epoch
     const int64_t n = (int64_t)p.B * p.L;
+    const bool capturing = stream_is_capturing(st);
 
     const int slot = step % JOT_PROFILE_RING;
-    if (s->profile) {
+    if (s->profile && !capturing) {
         s->prof_step[slot] = 0;
         if (hipEventRecord(s->prof0[slot], st) != hipSuccess) return JOT_ERR_HIP;
     }
     if (p.dtype == JOT_F32)
         hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotF32>, dim3(s->grid_reduce), dim3(JotF32::WG), 0, st,
-                           logits_dev, stride_b, stride_l, p.L, p.V, s->active(in), s->counters(in),
+                           logits_dev, stride_b, stride_l, p.L, p.V, s->frame,
                            s->at<JotPartial>(s->lay.partials), s->target_items, INFINITY);
     else
         hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotBF16>, dim3(s->grid_reduce), dim3(JotBF16::WG), 0, st,
-                           logits_dev, stride_b, stride_l, p.L, p.V, s->active(in), s->counters(in),
+                           logits_dev, stride_b, stride_l, p.L, p.V, s->frame,
                            s->at<JotPartial>(s->lay.partials), s->target_items, INFINITY);
     if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
-    if (s->profile) {
+    if (s->profile && !capturing) {
         if (hipEventRecord(s->prof1[slot], st) != hipSuccess) return JOT_ERR_HIP;
         s->prof_step[slot] = step;
     }
 
     JotDecideIO dio;
-    dio.active = s->active(in);
+    dio.active = nullptr;       // taken from the frame on the device
     dio.partials = s->at<JotPartial>(s->lay.partials);
     dio.resolved_bits = s->at<uint64_t>(s->lay.resolved_bits);
     dio.tokens = s->at<int32_t>(s->lay.tokens);
@@ -364,17 +387,15 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
 
     if (s->per_row_step) {
         hipLaunchKernelGGL(jot_row_step_kernel, dim3(p.B), dim3(JOT_WG), 0, st, s->decide, dio, sprm, sio,
-                           do_schedule ? 1 : 0, s->compact, step, s->counters(in), s->at<uint8_t>(s->lay.masked),
-                           s->row_counts(in), s->at<int32_t>(s->lay.row_block), s->row_counts(in ^ 1),
-                           s->at<int32_t>(s->lay.row_n_commit));
+                           do_schedule ? 1 : 0, s->compact, s->frame, s->at<uint8_t>(s->lay.masked),
+                           s->at<int32_t>(s->lay.row_block), s->at<int32_t>(s->lay.row_n_commit));
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     } else {
         hipLaunchKernelGGL(jot_decide_kernel, dim3((unsigned)((n + JOT_WG - 1) / JOT_WG)), dim3(JOT_WG), 0, st,
-                           s->decide, dio, step, s->counters(in));
+                           s->decide, dio, s->frame);
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
         if (do_schedule) {
-            hipLaunchKernelGGL(jot_schedule_kernel, dim3(p.B), dim3(JOT_WG), 0, st, sprm, sio, step,
-                               s->row_counts(in));
+            hipLaunchKernelGGL(jot_schedule_kernel, dim3(p.B), dim3(JOT_WG), 0, st, sprm, sio, s->frame);
             if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
         }
     }
@@ -382,18 +403,18 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
         const int grid = s->grid_sample;
         if (p.dtype == JOT_F32)
             hipLaunchKernelGGL(jot_sample_kernel<JotF32>, dim3(grid), dim3(JOT_WG), 0, st, logits_dev, stride_b,
-                               stride_l, p.L, p.V, s->active(in), s->at<int32_t>(s->lay.sample_list),
+                               stride_l, p.L, p.V, s->frame, s->at<int32_t>(s->lay.sample_list),
                                s->at<int32_t>(s->lay.sample_count), s->at<float>(s->lay.last_m1), uniforms_dev,
                                s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.last_final));
         else
             hipLaunchKernelGGL(jot_sample_kernel<JotBF16>, dim3(grid), dim3(JOT_WG), 0, st, logits_dev, stride_b,
-                               stride_l, p.L, p.V, s->active(in), s->at<int32_t>(s->lay.sample_list),
+                               stride_l, p.L, p.V, s->frame, s->at<int32_t>(s->lay.sample_list),
                                s->at<int32_t>(s->lay.sample_count), s->at<float>(s->lay.last_m1), uniforms_dev,
                                s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.last_final));
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     }
     s->step = step;
-    return enqueue_compaction(s, step, st, /*count_rows=*/!s->per_row_step);
+    return enqueue_compaction(s, /*creating=*/false, st, /*count_rows=*/!s->per_row_step);
 }
 
 int64_t jot_active_count(jot_state* s)
@@ -413,7 +434,11 @@ int64_t jot_anomaly_count(jot_state* s)
 const int32_t* jot_tokens(const jot_state* s) { return s ? s->at<int32_t>(s->lay.tokens) : nullptr; }
 const uint8_t* jot_masked(const jot_state* s) { return s ? s->at<uint8_t>(s->lay.masked) : nullptr; }
 const int32_t* jot_commit_step(const jot_state* s) { return s ? s->at<int32_t>(s->lay.commit_step) : nullptr; }
-const int32_t* jot_active_list(const jot_state* s) { return s ? s->active(s->cur) : nullptr; }
+const int32_t* jot_active_list(jot_state* s)
+{
+    if (!s || wait_done(s) != JOT_OK) return nullptr;
+    return s->active(s->host->parity);
+}
 
 const int32_t* jot_commit_log(jot_state* s, int64_t* n)
 {
@@ -426,7 +451,7 @@ const int32_t* jot_examined_list(jot_state* s, int64_t* n)
 {
     if (!s || !n || wait_done(s) != JOT_OK) return nullptr;
     *n = s->host->c.n_examined;
-    return s->active(s->cur ^ 1);
+    return s->active(s->host->parity ^ 1);
 }
 
 const int32_t* jot_last_token(const jot_state* s) { return s ? s->at<int32_t>(s->lay.last_token) : nullptr; }

@@ -89,26 +89,34 @@ __device__ __forceinline__ void jot_row_count(const JotCompactParams& prm, int32
     }
 }
 
+// `creating`: the pass that builds the first examined list when a state is created; it matches
+// no commit (step -1) and does not count as a step.
 __global__ __launch_bounds__(JOT_WG) void jot_row_count_kernel(
-    JotCompactParams prm, int32_t step, const uint8_t* __restrict__ masked,
+    JotCompactParams prm, JotFrame frame, int creating, const uint8_t* __restrict__ masked,
     const int32_t* __restrict__ commit_step, int32_t* __restrict__ row_block,
-    int32_t* __restrict__ row_n_active, int32_t* __restrict__ row_n_commit)
+    int32_t* __restrict__ row_n_commit)
 {
     __shared__ int lds[JOT_WAVES];
-    jot_row_count(prm, step, blockIdx.x, masked, commit_step, row_block, row_n_active, row_n_commit, lds);
+    const int half = frame.epoch->parity;
+    const int32_t step = creating ? -1 : frame.epoch->steps_done + 1;
+    jot_row_count(prm, step, blockIdx.x, masked, commit_step, row_block, frame.row_counts[half ^ 1], row_n_commit, lds);
 }
 
 // Pass 2: exclusive prefix over rows, then ordered writes.
 __global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
-    JotCompactParams prm, int32_t step, uint8_t* __restrict__ masked,
+    JotCompactParams prm, JotFrame frame, int creating, uint8_t* __restrict__ masked,
     const int32_t* __restrict__ commit_step, const int32_t* __restrict__ tokens,
-    const int32_t* __restrict__ row_block, const int32_t* __restrict__ row_n_active,
-    const int32_t* __restrict__ row_n_commit, const JotCounters* __restrict__ cnt_in,
-    JotCounters* __restrict__ cnt_out, int32_t* __restrict__ active_out,
+    const int32_t* __restrict__ row_block, const int32_t* __restrict__ row_n_commit,
     int32_t* __restrict__ commit_log, uint64_t* __restrict__ resolved_bits,
     const unsigned long long* __restrict__ anomalies, JotHostBlock* __restrict__ host_out,
     int32_t* __restrict__ sample_count)
 {
+    const int half = frame.epoch->parity;
+    const int32_t step = creating ? -1 : frame.epoch->steps_done + 1;
+    const int32_t* __restrict__ row_n_active = frame.row_counts[half ^ 1];
+    const JotCounters* __restrict__ cnt_in = frame.counters[half];
+    JotCounters* __restrict__ cnt_out = frame.counters[half ^ 1];
+    int32_t* __restrict__ active_out = frame.active[half ^ 1];
     __shared__ int lds[JOT_WAVES];
     __shared__ int wave_act[JOT_WAVES], wave_com[JOT_WAVES];
     const int b = blockIdx.x;
@@ -170,15 +178,31 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
         cnt_out->n_log = log_base + run_com;
         cnt_out->n_examined = cnt_in->n_active;
         cnt_out->reserved = 0;
-        // the same numbers straight into pinned host memory: the host reads them after waiting
-        // for the event recorded behind this kernel, so no copy command is needed
-        host_out->c.n_active = act_base + run_act;
-        host_out->c.n_log = log_base + run_com;
-        host_out->c.n_examined = cnt_in->n_active;
-        host_out->c.reserved = 0;
-        host_out->anomalies = *anomalies;
-        *sample_count = 0;            // the sampling work list of this step has been consumed
-        __threadfence_system();
+    }
+    // The workgroup that arrives last closes the step: every other workgroup has finished reading
+    // the epoch by then.  It flips the double buffers, counts the step, and stores the new
+    // counters straight into pinned host memory (the host reads them after synchronising).
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        const uint32_t arrived = atomicAdd(&frame.epoch->rows_done, 1u);
+        if (arrived == (uint32_t)prm.B - 1u) {
+            __threadfence();
+            // device-scope loads: the numbers were written by the workgroup of the last row
+            host_out->c.n_active = __hip_atomic_load(&cnt_out->n_active, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            host_out->c.n_log = __hip_atomic_load(&cnt_out->n_log, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            host_out->c.n_examined = __hip_atomic_load(&cnt_out->n_examined, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            host_out->c.reserved = 0;
+            host_out->anomalies = *anomalies;
+            const int32_t done = frame.epoch->steps_done + (creating ? 0 : 1);
+            host_out->steps_done = done;
+            host_out->parity = half ^ 1;
+            *sample_count = 0;            // the sampling work list of this step has been consumed
+            frame.epoch->rows_done = 0u;
+            frame.epoch->steps_done = done;
+            frame.epoch->parity = half ^ 1;
+            __threadfence_system();
+        }
     }
 }
 
@@ -186,7 +210,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
 __global__ __launch_bounds__(JOT_WG) void jot_init_copy_kernel(
     int64_t n, const int32_t* __restrict__ tokens_in, const uint8_t* __restrict__ masked_in,
     int32_t* __restrict__ tokens, uint8_t* __restrict__ masked, int32_t* __restrict__ commit_step,
-    JotCounters* __restrict__ cnt0, unsigned long long* __restrict__ anomalies)
+    JotCounters* __restrict__ cnt0, unsigned long long* __restrict__ anomalies, JotEpoch* __restrict__ epoch)
 {
     const int64_t k = (int64_t)blockIdx.x * JOT_WG + threadIdx.x;
     if (k < n) {
@@ -200,5 +224,9 @@ __global__ __launch_bounds__(JOT_WG) void jot_init_copy_kernel(
         cnt0->n_examined = 0;
         cnt0->reserved = 0;
         *anomalies = 0ull;
+        epoch->steps_done = 0;
+        epoch->parity = 0;
+        epoch->rows_done = 0u;
+        epoch->pad = 0;
     }
 }

@@ -10,7 +10,7 @@
 
 // Arrays the decision writes or reads, all in the caller's workspace.
 struct JotDecideIO {
-    const int32_t* active;
+    const int32_t* active;      // filled in by the kernel from the frame
     const JotPartial* partials;
     const uint64_t* resolved_bits;
     int32_t* tokens;
@@ -113,13 +113,15 @@ __device__ __forceinline__ void jot_decide_one(const JotDecideParams& prm, const
 }
 
 // One thread per examined position (used when rows are too long for the per-row kernel).
-__global__ __launch_bounds__(JOT_WG) void jot_decide_kernel(JotDecideParams prm, JotDecideIO io, int32_t step,
-                                                            const JotCounters* __restrict__ counters)
+__global__ __launch_bounds__(JOT_WG) void jot_decide_kernel(JotDecideParams prm, JotDecideIO io, JotFrame frame)
 {
-    const int64_t n_active = counters->n_active;
+    const int half = frame.epoch->parity;
+    const int32_t step = frame.epoch->steps_done + 1;
+    const int64_t n_active = frame.counters[half]->n_active;
     const int64_t r = (int64_t)blockIdx.x * JOT_WG + threadIdx.x;
     if (r >= n_active)
         return;
+    io.active = frame.active[half];
     const JotSplit sp = jot_plan_split(n_active, prm.V, prm.target_items, prm.split_align);
     jot_decide_one(prm, io, step, r, sp.S);
 }

@@ -58,10 +58,30 @@ struct JotCounters {
     int64_t reserved;
 };
 
+// Which half of the double buffers is current, and how many steps have been completed, live in
+// DEVICE memory: a launch never bakes in a step number or a buffer choice, so the same launch
+// sequence (for instance a captured HIP graph) can be replayed step after step.
+struct JotEpoch {
+    int32_t steps_done;   // completed steps; the running step is steps_done + 1
+    int32_t parity;       // half of the double buffers the running step READS
+    uint32_t rows_done;   // arrival counter of the last kernel of a step
+    int32_t pad;
+};
+
+// The double-buffered arrays, handed to every kernel by value.
+struct JotFrame {
+    JotEpoch* epoch;
+    int32_t* active[2];         // examined lists
+    JotCounters* counters[2];
+    int32_t* row_counts[2];     // per batch row: examined positions of that row
+};
+
 // Block the last compaction workgroup writes into host-visible pinned memory.
 struct JotHostBlock {
     JotCounters c;
     unsigned long long anomalies;
+    int32_t steps_done;
+    int32_t parity;       // half that the NEXT step reads (= where the current examined list is)
 };
 
 #define JOT_LOG2E 1.44269504088896340736f

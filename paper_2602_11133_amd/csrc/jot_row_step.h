@@ -12,17 +12,20 @@
 
 __global__ __launch_bounds__(JOT_WG) void jot_row_step_kernel(
     JotDecideParams dprm, JotDecideIO dio, JotScheduleParams sprm, JotScheduleIO sio, int do_schedule,
-    JotCompactParams cprm, int32_t step, const JotCounters* __restrict__ counters,
-    const uint8_t* __restrict__ masked, const int32_t* __restrict__ row_n_active_in,
-    int32_t* __restrict__ row_block, int32_t* __restrict__ row_n_active_out,
-    int32_t* __restrict__ row_n_commit)
+    JotCompactParams cprm, JotFrame frame, const uint8_t* __restrict__ masked,
+    int32_t* __restrict__ row_block, int32_t* __restrict__ row_n_commit)
 {
     __shared__ int lds[JOT_WAVES];
     __shared__ int wave_eq[JOT_WAVES];
+    const int half = frame.epoch->parity;
+    const int32_t step = frame.epoch->steps_done + 1;
+    const int32_t* row_n_active_in = frame.row_counts[half];
+    dio.active = frame.active[half];
+    sio.active = frame.active[half];
     const int b = blockIdx.x;
     const int64_t base = jot_row_base(row_n_active_in, b, lds);
     const int n = row_n_active_in[b];
-    const JotSplit sp = jot_plan_split(counters->n_active, dprm.V, dprm.target_items, dprm.split_align);
+    const JotSplit sp = jot_plan_split(frame.counters[half]->n_active, dprm.V, dprm.target_items, dprm.split_align);
 
     for (int j = threadIdx.x; j < n; j += JOT_WG)
         jot_decide_one(dprm, dio, step, base + j, sp.S);
@@ -31,5 +34,5 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_step_kernel(
         jot_schedule_row(sprm, sio, step, b, base, n, lds, wave_eq);
         __syncthreads();
     }
-    jot_row_count(cprm, step, b, masked, dio.commit_step, row_block, row_n_active_out, row_n_commit, lds);
+    jot_row_count(cprm, step, b, masked, dio.commit_step, row_block, frame.row_counts[half ^ 1], row_n_commit, lds);
 }

@@ -44,7 +44,7 @@ __device__ __forceinline__ double jot_wg_total(double v, double* lds)   // every
 template <class T>
 __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
     const void* __restrict__ logits, int64_t stride_b, int64_t stride_l, int L, int V,
-    const int32_t* __restrict__ active, const int32_t* __restrict__ sample_list,
+    JotFrame frame, const int32_t* __restrict__ sample_list,
     const int32_t* __restrict__ sample_count, const float* __restrict__ last_m1,
     const float* __restrict__ uniforms, int32_t* __restrict__ tokens, int32_t* __restrict__ last_final)
 {
@@ -54,6 +54,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
     __shared__ double lds[JOT_WAVES];
     __shared__ double wave_tot[JOT_WAVES];
     __shared__ int found_token;
+    const int32_t* __restrict__ active = frame.active[frame.epoch->parity];
     const int n_items = *sample_count;            // rows finalized this step, listed by the kernels before
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 

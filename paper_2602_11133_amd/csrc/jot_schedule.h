@@ -33,7 +33,7 @@ __device__ __forceinline__ int jot_wg_sum(int v, int* lds)      // v already sum
 // Arrays of the schedule pass, all in the caller's workspace.
 struct JotScheduleIO {
     const int32_t* n_transfer;      // [B] device, or NULL
-    const int32_t* active;
+    const int32_t* active;          // filled in by the kernel from the frame
     const float* last_p1;
     const float* last_conf;
     const int32_t* last_token;
@@ -160,11 +160,14 @@ __device__ __forceinline__ int64_t jot_row_base(const int32_t* __restrict__ row_
 }
 
 // Stand-alone launch (used when rows are too long for the per-row kernel): one workgroup per row.
-__global__ __launch_bounds__(JOT_WG) void jot_schedule_kernel(JotScheduleParams prm, JotScheduleIO io, int32_t step,
-                                                              const int32_t* __restrict__ row_n_active)
+__global__ __launch_bounds__(JOT_WG) void jot_schedule_kernel(JotScheduleParams prm, JotScheduleIO io, JotFrame frame)
 {
     __shared__ int lds[JOT_WAVES];
     __shared__ int wave_eq[JOT_WAVES];
+    const int half = frame.epoch->parity;
+    const int32_t step = frame.epoch->steps_done + 1;
+    const int32_t* row_n_active = frame.row_counts[half];
+    io.active = frame.active[half];
     const int b = blockIdx.x;
     const int64_t base = jot_row_base(row_n_active, b, lds);
     jot_schedule_row(prm, io, step, b, base, row_n_active[b], lds, wave_eq);

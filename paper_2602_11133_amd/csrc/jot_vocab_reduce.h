@@ -156,14 +156,15 @@ struct JotBF16 {
 template <class T>
 __global__ __launch_bounds__(T::WG) void jot_vocab_reduce_kernel(
     const void* __restrict__ logits, int64_t stride_b, int64_t stride_l, int L, int V,
-    const int32_t* __restrict__ active, const JotCounters* __restrict__ counters,
-    JotPartial* __restrict__ partials, int target_items, float pos_inf)
+    JotFrame frame, JotPartial* __restrict__ partials, int target_items, float pos_inf)
 {
     constexpr int VEC = T::VEC;
     constexpr int U = T::UNROLL;
     constexpr int WG = T::WG;
     constexpr int WAVES = WG / 64;
-    const int64_t n_active = counters->n_active;
+    const int half = frame.epoch->parity;
+    const int32_t* __restrict__ active = frame.active[half];
+    const int64_t n_active = frame.counters[half]->n_active;
     const JotSplit sp = jot_plan_split(n_active, V, target_items, WG * VEC * U);
     const int64_t n_items = n_active * sp.S;
     const int tid = threadIdx.x;
