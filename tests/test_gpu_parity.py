@@ -214,3 +214,68 @@ def test_config5_sampled_short(gpu):
     cfg = CONFIGS[5].replace(B=4, steps=16)
     run_parity(gpu, cfg, batch_rows=[0, 3], max_steps=16, sample=True,
                schedule=lambda n: (np.full(cfg.B, 16, np.int32), 0.0))
+
+
+# --------------------------------------------------------------------------- replay from a HIP graph
+
+@pytest.mark.parametrize("cid,scheduled", [(2, False), (1, False), (4, True)])
+def test_step_replayed_from_a_captured_graph(gpu, cid, scheduled):
+    """One jot_step is captured into a HIP graph and replayed for every later step of the decode
+    (step number and buffer parity live on the device, so nothing is baked into the launches).
+    Between replays the program does eager work (generating the next logits, reading results
+    back), and every replay is compared with the oracle."""
+    import paper_2602_11133_amd as J
+    from gen.device import DeviceGenerator
+    cfg = {1: CONFIGS[1].replace(L=32 + 40, steps=6, traj="sigmoid", conv="uniform"),
+           2: CONFIGS[2].replace(steps=20, L=64 + 96),
+           4: CONFIGS[4].replace(B=3, L=128 + 64, steps=64)}[cid]
+    say(f"[graph] {cfg.name} scheduled={scheduled}")
+    run = LockstepRun(cfg, threads=THREADS)
+    tokens0, masked0 = run.traj.initial_canvas()
+    g = gpu.GpuJot(gpu.params_of(cfg), tokens0, masked0)
+    dgen = DeviceGenerator(cfg, run.traj.target, run.traj.rival)
+    logits = dgen.alloc_logits(poison=True)
+    nt_host = np.ones(cfg.B, np.int32) if scheduled else None
+    nt_dev = torch.from_numpy(nt_host).cuda() if scheduled else None
+
+    def oracle_and_fill(n):
+        act_full = run.active_full()
+        rec, T, R, _ = run.next_step(nt_host, 0.0)
+        dgen.set_planted(T, R)
+        dgen.fill(logits, n, J.jot_active_list(g.h), g.active_count())
+        return act_full, rec
+
+    # step 1 eagerly
+    act_full, rec = oracle_and_fill(1)
+    g.step(logits, n_transfer=nt_host)
+    gpu.compare_step(g.last(), rec, act_full, TOL[cfg.dtype])
+    torch.cuda.synchronize()
+
+    # capture one step
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        st = torch.cuda.current_stream().cuda_stream
+        if scheduled:
+            J.jot_step_scheduled(g.h, logits.data_ptr(), cfg.L * cfg.V, cfg.V, nt_dev.data_ptr(), 0.0, st)
+        else:
+            J.jot_step(g.h, logits.data_ptr(), cfg.L * cfg.V, cfg.V, st)
+    torch.cuda.synchronize()
+
+    replays = 0
+    for n in range(2, cfg.steps + 16):
+        if run.state.active_count() == 0:
+            break
+        act_full, rec = oracle_and_fill(n)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        replays += 1
+        gpu.compare_step(g.last(), rec, act_full, TOL[cfg.dtype])
+        assert g.active_count() == run.state.active_count()
+    assert replays >= 3
+    np.testing.assert_array_equal(g.tokens(), run.state.tokens)
+    np.testing.assert_array_equal(g.masked(), run.state.masked)
+    want = np.array(run.state.commit_log, np.int32).reshape(-1, 3)
+    np.testing.assert_array_equal(g.commit_log(), want)          # step numbers keep counting on the device
+    g.close()
