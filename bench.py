@@ -32,9 +32,9 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # workload 5: see profiles/vocab_reduce_cfg5_hbm_traffic.md.  Valid only for the kernel sources
 # with these hashes and for that workload; otherwise bench.py reports null.
 MEASURED_TRAFFIC = {
-    "config": 5, "steps": 4, "bytes_per_launch": (38558961 + 2027) * 1024,
-    "sha256": {"jot_vocab_reduce.h": "d7b74f4290474b8456b96e31bb8012b97e69a315b8c606d3bda320f787276762",
-               "jot_device.h": "fdae872d300152b1e26e3c3c7c82bd89f03ac5634e217b88af4c3b7fd3868657"},
+    "config": 5, "steps": 4, "bytes_per_launch": (38559073 + 2027) * 1024,
+    "sha256": {"jot_vocab_reduce.h": "743d69b2ad15a65d2f3c50f6d353f88fb4707f10e68ad592f94b39157fc0d610",
+               "jot_device.h": "74734f6e5886fe8dc148ec3382d591ffcd23b828392147475546fbe12b8c44d9"},
 }
 
 
@@ -148,6 +148,8 @@ def main():
                          "remaining/steps_left of every row's examined positions (jot_step_scheduled)")
     ap.add_argument("--sample", action="store_true",
                     help="sampling-based finalization (jot_step_sampled with uniform numbers drawn beforehand)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture each step's launches into a HIP graph once and replay them in the timed loop")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
@@ -201,10 +203,32 @@ def main():
             dgen.fill(bufs[k], first_step + k, J.jot_active_list(g.h), n_act)
         torch.cuda.synchronize()
 
+    def enqueue_step(g, k, step_no, st):
+        frac = 1.0 / max(1, cfg.steps - step_no + 1) if args.schedule == "linear" else 0.0
+        if args.sample:
+            J.jot_step_sampled(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, 0, frac, uniforms[k].data_ptr(), st)
+        elif args.schedule == "linear":
+            J.jot_step_scheduled(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, 0, frac, st)
+        else:
+            J.jot_step(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, st)
+
+    def capture_graphs(g):
+        """One graph per resident logits buffer (the buffer address is part of the launch)."""
+        graphs = []
+        side = torch.cuda.Stream()
+        for k in range(resident):
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=side):
+                enqueue_step(g, k, 1, torch.cuda.current_stream().cuda_stream)
+            graphs.append(gr)
+        torch.cuda.synchronize()
+        return graphs
+
     def decode(g, n_steps, timed):
         """Runs n_steps steps in segments of `resident`; returns (seconds, [A_n], [reduce ms])."""
         total, examined, kms = 0.0, [], []
         done = 0
+        graphs = capture_graphs(g) if args.graph else None
         while done < n_steps:
             seg = min(resident, n_steps - done)
             fill_segment(g, done + 1, seg)
@@ -212,20 +236,16 @@ def main():
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for k in range(seg):
-                frac = 1.0 / max(1, cfg.steps - (done + k + 1) + 1) if args.schedule == "linear" else 0.0
-                if args.sample:
-                    J.jot_step_sampled(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, 0, frac,
-                                       uniforms[k].data_ptr(), stream)
-                elif args.schedule == "linear":
-                    J.jot_step_scheduled(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, 0, frac, stream)
+                if graphs:
+                    graphs[k].replay()
                 else:
-                    J.jot_step(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, stream)
+                    enqueue_step(g, k, done + k + 1, stream)
                 a_next = J.jot_active_count(g.h)        # the decode loop's termination test
                 examined.append(a_prev)
                 a_prev = a_next
             torch.cuda.synchronize()
             total += time.perf_counter() - t0
-            if timed:
+            if timed and not args.graph:
                 kms += [J.jot_profile_read(g.h, done + 1 + k) for k in range(seg)]
             done += seg
         return total, examined, kms
@@ -245,6 +265,8 @@ def main():
     elems = float(sum(examined)) * cfg.V
     value = elems / seconds
     k_bytes = elems * esz / K                       # algorithmic bytes per launch (average)
+    if not kms:                                     # --graph: no events inside the graph; whole-step time instead
+        kms = [seconds / K * 1e3] * K
     k_sec = sum(kms) * 1e-3 / K                     # average launch duration
     achieved = k_bytes / k_sec / 1e9
     out = {
@@ -256,13 +278,13 @@ def main():
         "config": {"workload": f"{cfg.name}: B={cfg.B}, L={cfg.L} ({cfg.gen_start} prompt + {cfg.n_gen} generated), "
                                f"V={cfg.V}, decode steps 1..{K}", "examined_positions_per_step": examined,
                    "conf_mode": cfg.conf_mode, "tau_max": cfg.tau_max, "tau_min": cfg.tau_min,
-                   "gamma": cfg.gamma, "D": cfg.D, "block_size": cfg.block_size, "schedule": args.schedule, "sampled_tokens": bool(args.sample),
+                   "gamma": cfg.gamma, "D": cfg.D, "block_size": cfg.block_size, "schedule": args.schedule, "sampled_tokens": bool(args.sample), "hip_graph": bool(args.graph),
                    "resident_logit_buffers": resident, "still_active_after": remaining, "anomalies": anomalies},
         "hbm_GBps_active_logits": elems * esz / seconds / 1e9,
         "pct_of_hbm_peak": 100.0 * elems * esz / seconds / 1e9 / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "kernel": "jot_vocab_reduce_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": measured_traffic(args.config, K) if args.dtype is None and args.schedule == "none" and not args.sample else None, "bytes_per_launch": k_bytes, "avg_launch_ms": k_sec * 1e3,
+                     "traffic": measured_traffic(args.config, K) if args.dtype is None and args.schedule == "none" and not args.sample and not args.graph else None, "bytes_per_launch": k_bytes, "avg_launch_ms": k_sec * 1e3,
                      "launch_ms": kms},
     }
     if not args.no_ceiling:
