@@ -83,8 +83,8 @@ def test_no_schedule_is_the_default_and_k_zero_changes_nothing():
 
 
 def test_unreachable_threshold_degrades_to_plain_top_k_decoding():
-    # "If no positions satisfy the confidence threshold, the step proceeds exactly as in standard
-    # decoding": with tau out of reach every step reveals exactly k per row, most confident first.
+    # Section 4.2 states that a step in which nothing clears its threshold is a step of the ordinary
+    # decoder: with tau out of reach every step reveals exactly k per row, most confident first.
     p, tokens, masked, logits, rng = case(2, conf_mode=O.CONF_MAXPROB, tau_max=2.0, tau_min=1.5)
     st = O.OracleState.init(p, tokens, masked)
     n = int(masked[0].sum())
