@@ -2,7 +2,7 @@
  * jot.h -- C ABI of the JoT token-finalization pass for AMD Instinct MI355X (gfx950).
  *
  * One call to jot_step() performs, for one denoising step n of a masked-diffusion decoder,
- * what the paper's Algorithm 1 does between "compute logits" and "apply transfer schedule":
+ * what the paper's Algorithm 1 does between the computation of the logits and the transfer schedule:
  *
  *   for every examined (still masked, eligible) position i:
  *     pi = softmax(l^i) over the vocabulary, no temperature          (Section 4.1, Confidence Metric)
