@@ -279,3 +279,39 @@ def test_step_replayed_from_a_captured_graph(gpu, cid, scheduled):
     want = np.array(run.state.commit_log, np.int32).reshape(-1, 3)
     np.testing.assert_array_equal(g.commit_log(), want)          # step numbers keep counting on the device
     g.close()
+
+
+def test_config5_full_size_repeats_bit_for_bit(gpu):
+    """Two decodes of the largest workload from the same inputs give identical bits everywhere
+    (confidences included): no result depends on the arrival order of workgroups or atomics."""
+    import paper_2602_11133_amd as J
+    from gen.device import DeviceGenerator
+    from gen.trajectory import Trajectory
+    cfg = CONFIGS[5]
+    tr = Trajectory(cfg)
+    tokens0, masked0 = tr.initial_canvas()
+    dgen = DeviceGenerator(cfg, tr.target, tr.rival)
+    logits = dgen.alloc_logits(poison=True)
+    nt = np.full(cfg.B, 4, np.int32)
+    u = np.random.default_rng(5).random((cfg.B, cfg.L), dtype=np.float32)
+    outs = []
+    for rep in range(2):
+        g = gpu.GpuJot(gpu.params_of(cfg), tokens0, masked0)
+        per_step = []
+        for n in range(1, 4):
+            T, R = tr.planted(n)
+            dgen.set_planted(T, R)
+            dgen.fill(logits, n, J.jot_active_list(g.h), g.active_count())
+            g.step(logits, n_transfer=nt, transfer_frac=0.01, uniforms=u)
+            last = g.last()
+            per_step.append({k: v.copy() for k, v in last.items()})
+        outs.append((per_step, g.tokens().copy(), g.commit_log().copy(), g.active_list().copy()))
+        say(f"  repetition {rep}: {outs[-1][2].shape[0]} finalized in 3 steps")
+        g.close()
+    a, b = outs
+    for sa, sb in zip(a[0], b[0]):
+        for k in sa:
+            np.testing.assert_array_equal(sa[k].view(np.uint8), sb[k].view(np.uint8))
+    for x, y in zip(a[1:], b[1:]):
+        np.testing.assert_array_equal(x, y)
+    assert a[2].shape[0] > 3 * cfg.B * 4
