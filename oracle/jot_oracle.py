@@ -36,6 +36,13 @@ floor(transfer_frac * examined_b)): an absolute count per row (a precomputed per
 in block-wise decoders) plus a fraction of what is still examined (as in decoders that reveal
 num_masked * (1 - s/t) per step).  Rows without a softmax are never selected.
 
+Row-wide early commit (the global rule Section 2 attributes to Prophet: once the top-2
+confidence gap exceeds a threshold, every remaining masked position is finalized at once; the
+thresholds quoted for it in Section 6.1, 7.5 / 5 / 2.5, are on the logit scale).  Here: per batch
+row, g_b = mean over the row's examined positions that have a softmax of the top-2 LOGIT gap
+m1 - m2; if g_b >= global_gap (a threshold the caller passes for this step, so a staged
+threshold is the caller's schedule) every such position of the row is finalized this step.
+
 Besides the paper's ratio r, two other confidence signals computed from the same
 (p1, p2) are selectable, because the workloads this is tested on quote
 thresholds on the probability scale: p1 itself, and the gap p1 - p2.
@@ -222,6 +229,8 @@ class StepRecord:
     sched: np.ndarray = None    # [A] bool: picked by the transfer schedule
     k_row: np.ndarray = None    # [B] number of positions the schedule picked per batch row
     final_token: np.ndarray = None  # [A] token written if finalized: argmax, or the sample
+    rowwide: np.ndarray = None      # [A] bool: finalized by the row-wide gap rule
+    gap_row: np.ndarray = None      # [B] mean top-2 logit gap of the row's examined positions (nan: none)
     cdf_margin: np.ndarray = None   # [A] with sampling: distance of u from the nearer edge of the
                                     #     chosen token's CDF interval (inf where nothing is sampled)
 
@@ -253,12 +262,13 @@ class OracleState:
         return int(self.active_list().size)
 
     def evaluate(self, rows: np.ndarray, n_transfer=None, transfer_frac: float = 0.0,
-                 sample_u=None) -> StepRecord:
+                 sample_u=None, global_gap=None) -> StepRecord:
         """Decisions of the next step for the given logit rows (rows[k] belongs to
         active_list()[k]) WITHOUT changing the state.  n_transfer ([B] ints) and transfer_frac
         describe the transfer schedule of this step; by default it reveals nothing.
         sample_u: optional [B, L] uniform numbers in [0, 1); when given, a finalized position
-        takes a token sampled from pi (inverse CDF at sample_u[b, i]) instead of the argmax."""
+        takes a token sampled from pi (inverse CDF at sample_u[b, i]) instead of the argmax.
+        global_gap: optional threshold of the row-wide early-commit rule for this step."""
         p = self.params
         act = self.active_list()
         if rows.shape[0] != act.size:
@@ -276,7 +286,8 @@ class OracleState:
         with np.errstate(invalid="ignore"):
             exit_ = ok & (conf >= tau)                          # Eq. 6
         sched, k_row = self._schedule(act, p1, ok, n_transfer, transfer_frac)
-        commit = exit_ | sched                                  # logical OR, uncapped
+        rowwide, gap_row = self._rowwide(act, m1, m2, ok, global_gap)
+        commit = exit_ | sched | rowwide                        # logical OR, uncapped
         final = a.copy()
         margin = np.full(act.size, np.inf)
         if sample_u is not None:
@@ -287,7 +298,24 @@ class OracleState:
                 final[k] = v
                 margin[k] = min(u - lo, hi - u)
         return StepRecord(self.step_index + 1, act, a, p1, p2, conf, tau, phi, commit, st,
-                          exit_, sched, k_row, final, margin)
+                          exit_, sched, k_row, final, rowwide, gap_row, margin)
+
+    def _rowwide(self, act, m1, m2, ok, global_gap):
+        """Row-wide early commit: mean top-2 logit gap of a row's examined positions >= threshold
+        finalizes all of them."""
+        p = self.params
+        rowwide = np.zeros(act.size, bool)
+        gap_row = np.full(p.B, np.nan)
+        if global_gap is None:
+            return rowwide, gap_row
+        row_of = act // p.L
+        for b in range(p.B):
+            mine = np.flatnonzero((row_of == b) & ok)
+            if mine.size:
+                gap_row[b] = float(np.mean(m1[mine] - m2[mine]))
+                if gap_row[b] >= global_gap:
+                    rowwide[mine] = True
+        return rowwide, gap_row
 
     def _schedule(self, act, p1, ok, n_transfer, transfer_frac):
         """Per batch row: the k positions with the largest p1 among the examined ones."""
@@ -324,15 +352,16 @@ class OracleState:
             self.commit_log.append((rec.step, pos, int(tok)))
         self.anomalies += int(rec.status.sum())
 
-    def step(self, rows: np.ndarray, n_transfer=None, transfer_frac: float = 0.0, sample_u=None) -> StepRecord:
-        rec = self.evaluate(rows, n_transfer, transfer_frac, sample_u)
+    def step(self, rows: np.ndarray, n_transfer=None, transfer_frac: float = 0.0, sample_u=None,
+             global_gap=None) -> StepRecord:
+        rec = self.evaluate(rows, n_transfer, transfer_frac, sample_u, global_gap)
         self.apply(rec)
         return rec
 
     def step_full(self, logits: np.ndarray, n_transfer=None, transfer_frac: float = 0.0,
-                  sample_u=None) -> StepRecord:
+                  sample_u=None, global_gap=None) -> StepRecord:
         """Convenience for small cases: logits is the whole [B, L, V] array."""
         p = self.params
         act = self.active_list()
         rows = logits.reshape(p.B * p.L, p.V)[act]
-        return self.step(rows, n_transfer, transfer_frac, sample_u)
+        return self.step(rows, n_transfer, transfer_frac, sample_u, global_gap)

@@ -11,6 +11,7 @@ import numpy as np
 import pytest
 
 import test_oracle_pins as P
+import test_oracle_rowwide_pins as R
 import test_oracle_schedule_pins as S
 from oracle import jot_oracle as O
 
@@ -48,6 +49,10 @@ def pin_battery():
         ("sched_fraction", S.test_fraction_one_reveals_everything_and_fraction_is_floored),
         ("sched_ties", S.test_equal_confidence_is_ranked_by_position_and_rows_without_softmax_are_skipped),
         ("sched_blocks", S.test_schedule_stays_inside_the_current_block_and_guarantees_termination),
+        ("rowwide_mean", R.test_mean_gap_and_all_or_nothing_per_row),
+        ("rowwide_inclusive", R.test_threshold_is_inclusive_and_off_by_default),
+        ("rowwide_or", R.test_rows_without_softmax_neither_count_nor_commit_and_rule_is_ored),
+        ("rowwide_blocks", R.test_block_mode_applies_the_rule_to_the_current_block_only),
     ]
     return b
 
@@ -137,9 +142,9 @@ def test_python_level_mistake_is_caught(name, monkeypatch):
 def test_sequential_update_is_caught(monkeypatch):
     orig = O.OracleState.evaluate
 
-    def evaluate_sequential(self, rows, n_transfer=None, transfer_frac=0.0):
+    def evaluate_sequential(self, rows, n_transfer=None, transfer_frac=0.0, sample_u=None, global_gap=None):
         # decide positions one at a time, each seeing the commits made before it in the same step
-        rec = orig(self, rows, n_transfer, transfer_frac)
+        rec = orig(self, rows, n_transfer, transfer_frac, sample_u, global_gap)
         masked = self.masked.copy()
         flat = masked.reshape(-1)
         for k in range(rec.active.size):
@@ -194,11 +199,50 @@ def test_schedule_mistake_is_caught(kind, monkeypatch):
     assert failing_pins(), f"no pin notices: {kind}"
 
 
+def _rowwide_variant(kind):
+    def _rowwide(self, act, m1, m2, ok, global_gap):
+        p = self.params
+        rowwide = np.zeros(act.size, bool)
+        gap_row = np.full(p.B, np.nan)
+        if global_gap is None:
+            return rowwide, gap_row
+        row_of = act // p.L
+        if kind == "one_statistic_for_the_whole_batch":
+            mine = np.flatnonzero(ok)
+            g = float(np.mean(m1[mine] - m2[mine])) if mine.size else np.nan
+            gap_row[:] = g
+            if g >= global_gap:
+                rowwide[mine] = True
+            return rowwide, gap_row
+        for b in range(p.B):
+            mine = np.flatnonzero((row_of == b) & (ok if kind != "counts_rows_without_softmax" else True))
+            if mine.size:
+                d = m1[mine] - m2[mine]
+                if kind == "largest_gap_instead_of_mean":
+                    gap_row[b] = float(np.max(d))
+                elif kind == "probability_gap":
+                    gap_row[b] = float(np.mean(1 - np.exp(-d)))
+                else:
+                    gap_row[b] = float(np.nanmean(d))
+                fire = gap_row[b] > global_gap if kind == "strict_comparison" else gap_row[b] >= global_gap
+                if fire:
+                    rowwide[mine] = True
+        return rowwide, gap_row
+    return _rowwide
+
+
+@pytest.mark.parametrize("kind", ["one_statistic_for_the_whole_batch", "largest_gap_instead_of_mean",
+                                  "probability_gap", "strict_comparison", "counts_rows_without_softmax"])
+def test_rowwide_mistake_is_caught(kind, monkeypatch):
+    monkeypatch.setattr(O.OracleState, "_rowwide", _rowwide_variant(kind))
+    assert failing_pins(), f"no pin notices: {kind}"
+
+
 def test_and_instead_of_or_is_caught(monkeypatch):
     orig = O.OracleState.evaluate
 
-    def evaluate_and(self, rows, n_transfer=None, transfer_frac=0.0):
-        rec = orig(self, rows, n_transfer, transfer_frac)
+    def evaluate_and(self, rows, n_transfer=None, transfer_frac=0.0, sample_u=None, global_gap=None):
+        rec = orig(self, rows, n_transfer, transfer_frac, sample_u, global_gap)
         if n_transfer is not None or transfer_frac:
             rec.commit = rec.exit & rec.sched
         return rec
