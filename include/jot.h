@@ -151,6 +151,29 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
                      const int32_t* n_transfer_dev, float transfer_frac, const float* uniforms_dev,
                      void* stream);
 
+/*
+ * The general step.  `opt` gathers the optional rules of a step; NULL or an all-zero struct is
+ * plain jot_step.  jot_step, jot_step_scheduled and jot_step_sampled are shorthands for it.
+ *
+ * Row-wide early commit (enable_global_gap != 0): the global rule the paper's related-work section
+ * describes for Prophet -- once the top-2 confidence gap clears a threshold, every remaining
+ * masked position is finalized at once.  Here, per batch row: if the MEAN of the top-2 logit gaps
+ * l_(1) - l_(2) over the row's examined positions that have a softmax is >= global_gap, all of
+ * those positions are finalized this step (argmax, or sampled if uniforms_dev is given), OR-ed
+ * with the early exit and the schedule.  A staged threshold (e.g. 7.5 / 5 / 2.5 as decoding
+ * progresses) is simply a different global_gap per call.
+ */
+typedef struct {
+    const int32_t* n_transfer_dev;   /* transfer schedule, see jot_step_scheduled; may be NULL      */
+    float          transfer_frac;    /* in [0, 1]                                                   */
+    const float*   uniforms_dev;     /* sampling, see jot_step_sampled; NULL = argmax               */
+    int32_t        enable_global_gap;/* != 0: apply the row-wide early-commit rule this step        */
+    float          global_gap;       /* its threshold (finite)                                      */
+} jot_step_options;
+
+int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
+                const jot_step_options* opt, void* stream);
+
 /* Number of positions the NEXT step would examine (0 = decoding finished).  Waits for the work
  * enqueued so far on this state.  <0: JOT_ERR_*. */
 int64_t jot_active_count(jot_state* s);
@@ -187,7 +210,8 @@ const float*   jot_last_conf(const jot_state* s);
 const float*   jot_last_p1(const jot_state* s);
 const float*   jot_last_p2(const jot_state* s);
 const float*   jot_last_tau(const jot_state* s);
-/* per examined position: bit 0 = passed Eq. 6, bit 1 = picked by the transfer schedule */
+/* per examined position: bit 0 = passed Eq. 6, bit 1 = picked by the transfer schedule,
+ * bit 2 = finalized by the row-wide early-commit rule */
 const uint8_t* jot_last_flags(const jot_state* s);
 
 /*

@@ -11,7 +11,7 @@ import numpy as np
 __all__ = [
     "JOT_F32", "JOT_BF16", "JOT_CONF_RATIO", "JOT_CONF_MAXPROB", "JOT_CONF_PROBGAP",
     "JotParams", "JotError", "load_library", "library_path",
-    "jot_workspace_bytes", "jot_init_state", "jot_step", "jot_step_scheduled", "jot_step_sampled", "jot_last_flags", "jot_last_final_token", "jot_active_count", "jot_step_index",
+    "jot_workspace_bytes", "jot_init_state", "jot_step", "jot_step_scheduled", "jot_step_sampled", "jot_step_ex", "JotStepOptions", "jot_last_flags", "jot_last_final_token", "jot_active_count", "jot_step_index",
     "jot_anomaly_count", "jot_tokens", "jot_masked", "jot_commit_step", "jot_active_list",
     "jot_commit_log", "jot_examined_list", "jot_last_token", "jot_last_conf", "jot_last_p1",
     "jot_last_p2", "jot_last_tau", "jot_profile_enable", "jot_profile_read", "jot_release",
@@ -32,6 +32,14 @@ class JotParams(ctypes.Structure):
         ("tau_max", ctypes.c_float), ("tau_min", ctypes.c_float), ("gamma", ctypes.c_float),
         ("D", ctypes.c_int32), ("eps", ctypes.c_float),
         ("gen_start", ctypes.c_int32), ("block_size", ctypes.c_int32),
+    ]
+
+
+class JotStepOptions(ctypes.Structure):
+    _fields_ = [
+        ("n_transfer_dev", ctypes.c_void_p), ("transfer_frac", ctypes.c_float),
+        ("uniforms_dev", ctypes.c_void_p), ("enable_global_gap", ctypes.c_int32),
+        ("global_gap", ctypes.c_float),
     ]
 
 
@@ -65,6 +73,7 @@ def load_library():
         "jot_step": (ctypes.c_int, [vp, vp, i64, i64, vp]),
         "jot_step_scheduled": (ctypes.c_int, [vp, vp, i64, i64, vp, ctypes.c_float, vp]),
         "jot_step_sampled": (ctypes.c_int, [vp, vp, i64, i64, vp, ctypes.c_float, vp, vp]),
+        "jot_step_ex": (ctypes.c_int, [vp, vp, i64, i64, ctypes.POINTER(JotStepOptions), vp]),
         "jot_last_flags": (vp, [vp]), "jot_last_final_token": (vp, [vp]),
         "jot_active_count": (i64, [vp]),
         "jot_step_index": (i32, [vp]),
@@ -126,6 +135,12 @@ def jot_step_sampled(s: int, logits_dev: int, stride_b: int, stride_l: int, n_tr
     _check(load_library().jot_step_sampled(s, logits_dev, stride_b, stride_l, n_transfer_dev or None,
                                            float(transfer_frac), uniforms_dev or None, stream),
            "jot_step_sampled")
+
+
+def jot_step_ex(s: int, logits_dev: int, stride_b: int, stride_l: int, opt: "JotStepOptions | None",
+                stream: int = 0) -> None:
+    _check(load_library().jot_step_ex(s, logits_dev, stride_b, stride_l,
+                                      ctypes.byref(opt) if opt is not None else None, stream), "jot_step_ex")
 
 
 def jot_active_count(s: int) -> int:

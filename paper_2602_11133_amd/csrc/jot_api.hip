@@ -33,7 +33,7 @@ constexpr int kPerRowStepMax = 2048;   // longest per-row examined list handled 
 
 struct Layout {
     int64_t tokens, masked, commit_step, resolved_bits, active0, active1, counters, epoch, anomalies,
-        partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, last_m1, last_final, sample_list, sample_count, row_block, row_n_active0, row_n_active1,
+        partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, last_m1, last_gap, last_final, sample_list, sample_count, row_block, row_n_active0, row_n_active1,
         row_n_commit, commit_log, total;
     int64_t n_partials;
     int32_t words_per_row;
@@ -83,6 +83,7 @@ Layout make_layout(const jot_params* p, int target_items)
     l.last_tau = take(n * 4);
     l.last_flags = take(n);
     l.last_m1 = take(n * 4);
+    l.last_gap = take(n * 4);
     l.last_final = take(n * 4);
     l.sample_list = take(n * 4);
     l.sample_count = take(4);
@@ -313,7 +314,26 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
                      const int32_t* n_transfer_dev, float transfer_frac, const float* uniforms_dev,
                      void* stream)
 {
+    jot_step_options opt;
+    memset(&opt, 0, sizeof opt);
+    opt.n_transfer_dev = n_transfer_dev;
+    opt.transfer_frac = transfer_frac;
+    opt.uniforms_dev = uniforms_dev;
+    return jot_step_ex(s, logits_dev, stride_b, stride_l, &opt, stream);
+}
+
+int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
+                const jot_step_options* opt, void* stream)
+{
+    jot_step_options none;
+    memset(&none, 0, sizeof none);
+    if (!opt) opt = &none;
+    const int32_t* n_transfer_dev = opt->n_transfer_dev;
+    const float transfer_frac = opt->transfer_frac;
+    const float* uniforms_dev = opt->uniforms_dev;
+    const bool do_rowwide = opt->enable_global_gap != 0;
     if (!s || !logits_dev) return JOT_ERR_NULL_POINTER;
+    if (do_rowwide && !isfinite(opt->global_gap)) return JOT_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(uniforms_dev) % 4) return JOT_ERR_MISALIGNED;
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return JOT_ERR_NO_DEVICE;
@@ -366,6 +386,7 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
     dio.last_tau = s->at<float>(s->lay.last_tau);
     dio.last_flags = s->at<uint8_t>(s->lay.last_flags);
     dio.last_m1 = s->at<float>(s->lay.last_m1);
+    dio.last_gap = s->at<float>(s->lay.last_gap);
     dio.last_final = s->at<int32_t>(s->lay.last_final);
     dio.sample_list = uniforms_dev ? s->at<int32_t>(s->lay.sample_list) : nullptr;
     dio.sample_count = s->at<int32_t>(s->lay.sample_count);
@@ -373,11 +394,15 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
     const bool do_schedule = n_transfer_dev || transfer_frac > 0.0f;
     JotScheduleParams sprm;
     sprm.B = p.B; sprm.L = p.L; sprm.transfer_frac = transfer_frac;
+    sprm.do_schedule = do_schedule ? 1 : 0;
+    sprm.do_rowwide = do_rowwide ? 1 : 0;
+    sprm.global_gap = do_rowwide ? opt->global_gap : 0.0f;
     JotScheduleIO sio;
     sio.n_transfer = n_transfer_dev;
     sio.active = dio.active;
     sio.last_p1 = dio.last_p1;
     sio.last_conf = dio.last_conf;
+    sio.last_gap = dio.last_gap;
     sio.last_token = dio.last_token;
     sio.last_flags = dio.last_flags;
     sio.tokens = dio.tokens;
@@ -387,15 +412,15 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
 
     if (s->per_row_step) {
         hipLaunchKernelGGL(jot_row_step_kernel, dim3(p.B), dim3(JOT_WG), 0, st, s->decide, dio, sprm, sio,
-                           do_schedule ? 1 : 0, s->compact, s->frame, s->at<uint8_t>(s->lay.masked),
+                           s->compact, s->frame, s->at<uint8_t>(s->lay.masked),
                            s->at<int32_t>(s->lay.row_block), s->at<int32_t>(s->lay.row_n_commit));
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     } else {
         hipLaunchKernelGGL(jot_decide_kernel, dim3((unsigned)((n + JOT_WG - 1) / JOT_WG)), dim3(JOT_WG), 0, st,
                            s->decide, dio, s->frame);
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
-        if (do_schedule) {
-            hipLaunchKernelGGL(jot_schedule_kernel, dim3(p.B), dim3(JOT_WG), 0, st, sprm, sio, s->frame);
+        if (do_schedule || do_rowwide) {
+            hipLaunchKernelGGL(jot_row_rules_kernel, dim3(p.B), dim3(JOT_WG), 0, st, sprm, sio, s->frame);
             if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
         }
     }

@@ -22,6 +22,7 @@ struct JotDecideIO {
     float* last_tau;
     uint8_t* last_flags;
     float* last_m1;
+    float* last_gap;            // top-2 logit gap m1 - m2 (+inf when only one logit is finite)
     int32_t* last_final;
     int32_t* sample_list;       // NULL unless this step samples its tokens
     int32_t* sample_count;
@@ -105,6 +106,7 @@ __device__ __forceinline__ void jot_decide_one(const JotDecideParams& prm, const
     io.last_token[r] = idx;
     io.last_final[r] = idx;            // the sampling kernel, if it runs, overwrites this
     io.last_m1[r] = m1;
+    io.last_gap[r] = m1 - m2;
     io.last_flags[r] = commit ? 1 : 0;
     io.last_conf[r] = has_softmax ? conf : __uint_as_float(0x7fc00000u);
     io.last_p1[r] = p1;

@@ -1,6 +1,6 @@
 // Per-row step kernel: for canvases whose rows examine at most a couple of thousand positions
 // per step (every workload of the paper's shape) the decision (Eq. 2 - Eq. 6), the optional
-// transfer schedule and the per-row counting pass of the compaction run in ONE launch, one
+// transfer schedule, the optional row-wide early commit and the per-row counting pass of the compaction run in ONE launch, one
 // workgroup per batch row, instead of three.  Nothing crosses rows here: a row's slice of the
 // examined list is found from the per-row counts of the previous step, and the counts for the
 // next step go to the other half of a double buffer (a workgroup that starts late must still
@@ -11,12 +11,13 @@
 #include "jot_schedule.h"
 
 __global__ __launch_bounds__(JOT_WG) void jot_row_step_kernel(
-    JotDecideParams dprm, JotDecideIO dio, JotScheduleParams sprm, JotScheduleIO sio, int do_schedule,
+    JotDecideParams dprm, JotDecideIO dio, JotScheduleParams sprm, JotScheduleIO sio,
     JotCompactParams cprm, JotFrame frame, const uint8_t* __restrict__ masked,
     int32_t* __restrict__ row_block, int32_t* __restrict__ row_n_commit)
 {
     __shared__ int lds[JOT_WAVES];
     __shared__ int wave_eq[JOT_WAVES];
+    __shared__ double dlds[JOT_WAVES];
     const int half = frame.epoch->parity;
     const int32_t step = frame.epoch->steps_done + 1;
     const int32_t* row_n_active_in = frame.row_counts[half];
@@ -30,8 +31,12 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_step_kernel(
     for (int j = threadIdx.x; j < n; j += JOT_WG)
         jot_decide_one(dprm, dio, step, base + j, sp.S);
     __syncthreads();                       // this row's results are visible to the whole workgroup
-    if (do_schedule) {
+    if (sprm.do_schedule) {
         jot_schedule_row(sprm, sio, step, b, base, n, lds, wave_eq);
+        __syncthreads();
+    }
+    if (sprm.do_rowwide) {
+        jot_rowwide_row(sprm, sio, step, base, n, dlds, lds);
         __syncthreads();
     }
     jot_row_count(cprm, step, b, masked, dio.commit_step, row_block, frame.row_counts[half ^ 1], row_n_commit, lds);

@@ -17,6 +17,9 @@
 struct JotScheduleParams {
     int32_t B, L;
     float transfer_frac;
+    int32_t do_schedule;        // transfer schedule requested this step
+    int32_t do_rowwide;         // row-wide early commit requested this step
+    float global_gap;           // its threshold on the mean top-2 logit gap
 };
 
 __device__ __forceinline__ int jot_wg_sum(int v, int* lds)      // v already summed per wave in lane 0
@@ -36,6 +39,7 @@ struct JotScheduleIO {
     const int32_t* active;          // filled in by the kernel from the frame
     const float* last_p1;
     const float* last_conf;
+    const float* last_gap;
     const int32_t* last_token;
     uint8_t* last_flags;
     int32_t* tokens;
@@ -149,6 +153,59 @@ __device__ __forceinline__ void jot_schedule_row(const JotScheduleParams& prm, c
     }
 }
 
+// Row-wide early commit (the global rule of Section 2: once the top-2 gap clears a threshold,
+// every remaining masked position is finalized at once).  Per batch row: if the mean of the
+// top-2 LOGIT gaps m1 - m2 over the row's examined positions that have a softmax reaches
+// global_gap, all of them are finalized.  The mean is accumulated in double in a fixed order.
+// Called by every thread of the workgroup; dlds: JOT_WAVES doubles, lds: JOT_WAVES ints.
+__device__ __forceinline__ void jot_rowwide_row(const JotScheduleParams& prm, const JotScheduleIO& io,
+                                                int32_t step, int64_t base, int n, double* dlds, int* lds)
+{
+    double part = 0.0;
+    int cnt = 0;
+    for (int j = threadIdx.x; j < n; j += JOT_WG) {
+        const float c = io.last_conf[base + j];
+        if (c == c) {                       // rows without a softmax carry a NaN confidence
+            part += (double)io.last_gap[base + j];
+            cnt += 1;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        part += __shfl_xor(part, off, 64);
+        cnt += __shfl_xor(cnt, off, 64);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        dlds[threadIdx.x >> 6] = part;
+        lds[threadIdx.x >> 6] = cnt;
+    }
+    __syncthreads();
+    double sum = 0.0;
+    int total = 0;
+#pragma unroll
+    for (int k = 0; k < JOT_WAVES; ++k) {
+        sum += dlds[k];
+        total += lds[k];
+    }
+    __syncthreads();
+    if (total == 0 || !(sum / (double)total >= (double)prm.global_gap))
+        return;
+    for (int j = threadIdx.x; j < n; j += JOT_WG) {
+        const int64_t r = base + j;
+        const float c = io.last_conf[r];
+        if (c == c) {
+            const int pos = io.active[r];
+            io.last_flags[r] |= 4;
+            if (io.commit_step[pos] != step) {
+                io.tokens[pos] = io.last_token[r];
+                io.commit_step[pos] = step;
+                if (io.sample_list)
+                    io.sample_list[atomicAdd(io.sample_count, 1)] = (int32_t)r;
+            }
+        }
+    }
+}
+
 // Sum over the batch rows before b of the per-row examined counts = start of row b's slice.
 __device__ __forceinline__ int64_t jot_row_base(const int32_t* __restrict__ row_n_active, int b, int* lds)
 {
@@ -159,16 +216,23 @@ __device__ __forceinline__ int64_t jot_row_base(const int32_t* __restrict__ row_
     return jot_wg_sum(pa, lds);
 }
 
-// Stand-alone launch (used when rows are too long for the per-row kernel): one workgroup per row.
-__global__ __launch_bounds__(JOT_WG) void jot_schedule_kernel(JotScheduleParams prm, JotScheduleIO io, JotFrame frame)
+// Stand-alone launch of the per-row rules (used when rows are too long for the per-row kernel).
+__global__ __launch_bounds__(JOT_WG) void jot_row_rules_kernel(JotScheduleParams prm, JotScheduleIO io, JotFrame frame)
 {
     __shared__ int lds[JOT_WAVES];
     __shared__ int wave_eq[JOT_WAVES];
+    __shared__ double dlds[JOT_WAVES];
     const int half = frame.epoch->parity;
     const int32_t step = frame.epoch->steps_done + 1;
     const int32_t* row_n_active = frame.row_counts[half];
     io.active = frame.active[half];
     const int b = blockIdx.x;
     const int64_t base = jot_row_base(row_n_active, b, lds);
-    jot_schedule_row(prm, io, step, b, base, row_n_active[b], lds, wave_eq);
+    const int n = row_n_active[b];
+    if (prm.do_schedule) {
+        jot_schedule_row(prm, io, step, b, base, n, lds, wave_eq);
+        __syncthreads();
+    }
+    if (prm.do_rowwide)
+        jot_rowwide_row(prm, io, step, base, n, dlds, lds);
 }

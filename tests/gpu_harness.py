@@ -44,9 +44,22 @@ class GpuJot:
             pass
 
     def step(self, logits: torch.Tensor, stride_b=None, stride_l=None, n_transfer=None, transfer_frac=0.0,
-             uniforms=None):
+             uniforms=None, global_gap=None):
         sb = logits.stride(0) if stride_b is None else stride_b
         sl = logits.stride(1) if stride_l is None else stride_l
+        if global_gap is not None:                       # the general entry point
+            opt = J.JotStepOptions()
+            if n_transfer is not None:
+                self._nt = torch.from_numpy(np.ascontiguousarray(n_transfer, np.int32)).to(self.dev)
+                opt.n_transfer_dev = self._nt.data_ptr()
+            opt.transfer_frac = transfer_frac
+            if uniforms is not None:
+                self._u = torch.from_numpy(np.ascontiguousarray(uniforms, np.float32)).to(self.dev)
+                opt.uniforms_dev = self._u.data_ptr()
+            opt.enable_global_gap = 1
+            opt.global_gap = global_gap
+            J.jot_step_ex(self.h, logits.data_ptr(), sb, sl, opt, self.stream)
+            return
         if uniforms is not None:
             self._u = torch.from_numpy(np.ascontiguousarray(uniforms, np.float32)).to(self.dev)
             nt = 0
@@ -144,5 +157,7 @@ def compare_step(gpu_last: dict, rec, act_full: np.ndarray, tol: float, select=N
     np.testing.assert_array_equal((g["flags"] & 1).astype(bool), want_exit)
     want_sched = rec.sched if rec.sched is not None else np.zeros_like(rec.commit)
     np.testing.assert_array_equal((g["flags"] & 2).astype(bool), want_sched)
+    want_rowwide = rec.rowwide if rec.rowwide is not None else np.zeros_like(rec.commit)
+    np.testing.assert_array_equal((g["flags"] & 4).astype(bool), want_rowwide)
     want_final = rec.final_token if rec.final_token is not None else rec.token
     np.testing.assert_array_equal(g["final"][rec.commit], want_final[rec.commit])   # bit exact

@@ -70,7 +70,7 @@ class LockstepRun:
         rng = np.random.default_rng([self.cfg.seed, 0x756E6966, step])
         return rng.random((self.cfg.B, self.cfg.L), dtype=np.float32)
 
-    def next_step(self, n_transfer=None, transfer_frac: float = 0.0, sample_u=None):
+    def next_step(self, n_transfer=None, transfer_frac: float = 0.0, sample_u=None, global_gap=None):
         """Advance the oracle one step.  Returns (rec, T, R, rows) where rec.active is in
         sub-batch numbering, T/R are the final planted tables of this step (full canvas) and
         rows are the logit rows the oracle saw (a view valid until the next call).
@@ -86,9 +86,18 @@ class LockstepRun:
         rows = self.gen.rows(n, act_full, T, R)
         u_sub = None if sample_u is None else sample_u[self.batch_rows]
         redraw = np.random.default_rng([self.cfg.seed, 0x72656472, n])
-        rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub)
+        rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub, global_gap)
         for _ in range(MAX_BUMPS):
             bad = too_close(rec, self.cfg.L)
+            amount = {}                           # entry -> how much to raise its target logit (default 0.25)
+            if global_gap is not None:            # a row's mean gap too close to the row-wide threshold:
+                scale = max(1.0, abs(global_gap))
+                near = np.flatnonzero(np.abs(rec.gap_row - global_gap) < GUARD * scale)
+                row_of = rec.active // self.cfg.L
+                for b in near:                    # move the mean by raising one target logit of that row
+                    mine = np.flatnonzero((row_of == b) & (rec.status == 0))
+                    amount[int(mine[0])] = 4.0 * GUARD * scale * mine.size
+                    bad = np.union1d(bad, mine[:1])
             if sample_u is not None:
                 edge = np.flatnonzero(rec.commit & (rec.cdf_margin < GUARD_U))
                 if edge.size:                   # a new uniform number for that position (an input)
@@ -97,17 +106,17 @@ class LockstepRun:
                         sample_u[bb, ii] = redraw.random(dtype=np.float32)
                     u_sub = sample_u[self.batch_rows]
                     if bad.size == 0:
-                        rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub)
+                        rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub, global_gap)
                         continue
             if bad.size == 0:
                 break
             for k in bad:
-                tr.bump(n, int(act_full[k]))
+                tr.bump(n, int(act_full[k]), amount.get(int(k), 0.25))
             self.n_bumps += int(bad.size)
             T, R = tr.planted(n)
             fixer = HostGenerator(self.cfg, tr.target, tr.rival, 1)
             rows[bad] = fixer.rows(n, act_full[bad], T, R)
-            rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub)
+            rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub, global_gap)
         else:
             raise RuntimeError("could not clear the guard band")
         st.apply(rec)

@@ -64,7 +64,7 @@ def to_device(logits: np.ndarray, dtype: int, stride_l: int):
 
 
 def check_case(gpu, p: O.OracleParams, tokens, masked, logit_seq, stride_pad=0, tol=None, clear=True,
-               schedule=None, uniforms=None):
+               schedule=None, uniforms=None, global_gap=None):
     """schedule: optional list of (n_transfer, frac) per step.  uniforms: optional list of [B, L]
     float32 arrays per step (sampling-based finalization); numbers that fall within GUARD_U of
     an edge of the chosen token's CDF interval are redrawn here (they are inputs)."""
@@ -88,6 +88,7 @@ def check_case(gpu, p: O.OracleParams, tokens, masked, logit_seq, stride_pad=0, 
             logits = bf16_bits_to_f32(f32_to_bf16_bits(logits)).reshape(logits.shape)
         nt, frac = schedule[n - 1] if schedule else (None, 0.0)
         frac = float(np.float32(frac))
+        gg = None if global_gap is None else float(np.float32(global_gap[n - 1]))
         if clear:
             clear_guard_band(st, logits, nt, frac)
             if p.dtype == O.BF16:
@@ -98,15 +99,18 @@ def check_case(gpu, p: O.OracleParams, tokens, masked, logit_seq, stride_pad=0, 
             u = np.array(uniforms[n - 1], np.float32)
             redraw = np.random.default_rng(1000 + n)
             for _ in range(100):
-                probe = st.evaluate(as_rows(logits.reshape(p.B * p.L, p.V)[act], p.dtype), nt, frac, u)
+                probe = st.evaluate(as_rows(logits.reshape(p.B * p.L, p.V)[act], p.dtype), nt, frac, u, gg)
                 edge = np.flatnonzero(probe.commit & (probe.cdf_margin < GUARD_U))
                 if edge.size == 0:
                     break
                 for k in edge:
                     u.reshape(-1)[act[k]] = redraw.random(dtype=np.float32)
-        rec = st.step(as_rows(logits.reshape(p.B * p.L, p.V)[act], p.dtype), nt, frac, u)
+        rec = st.step(as_rows(logits.reshape(p.B * p.L, p.V)[act], p.dtype), nt, frac, u, gg)
+        if gg is not None:
+            assert np.all(~(np.abs(rec.gap_row - gg) < GUARD * max(1.0, abs(gg)))), "row mean sits on the threshold"
         dev = to_device(logits, p.dtype, stride_l)
-        g.step(dev, stride_b=p.L * stride_l, stride_l=stride_l, n_transfer=nt, transfer_frac=frac, uniforms=u)
+        g.step(dev, stride_b=p.L * stride_l, stride_l=stride_l, n_transfer=nt, transfer_frac=frac, uniforms=u,
+               global_gap=gg)
         gpu.compare_step(g.last(), rec, act, tol)
         np.testing.assert_array_equal(g.tokens(), st.tokens)
         np.testing.assert_array_equal(g.masked(), st.masked)
@@ -476,3 +480,25 @@ def test_fill_values_and_out_of_range_maxima(gpu, dtype):
     toks, msk, log, last = check_case(gpu, p, np.zeros((1, L), np.int32), np.ones((1, L), bool), [lg], clear=False)
     assert msk[0].tolist() == [False, False, False, False, True, True, True, False]
     assert toks[0, 7] == 5 and toks[0, 0] < 30_000 and toks[0, 1] >= 60_000
+
+
+# --------------------------------------------------------------------------- row-wide early commit
+
+@pytest.mark.parametrize("L,block", [(70, 0), (2600, 0), (300, 32)])
+def test_rowwide_rule(gpu, L, block):
+    # rows with very different mean gaps: some fire, some do not; long rows take the separate kernels
+    B, V = 4, 60
+    rng = np.random.default_rng(80 + L)
+    p = O.OracleParams(B=B, L=L, V=V, dtype=O.F32, conf_mode=O.CONF_RATIO, tau_max=1e6, tau_min=1e6, D=4,
+                       gen_start=6, block_size=block)
+    masked = np.zeros((B, L), bool)
+    masked[:, 6:] = rng.random((B, L - 6)) < 0.9
+    lg = rng.standard_normal((B, L, V)).astype(np.float32)
+    lg[1, :, 7] += 9.0                                   # decided row
+    lg[3, :, 2] += 4.0                                   # in between
+    lg[2, 10, 5] = np.nan                                # a row without a softmax does not count
+    lg[2, 11, :] = -np.inf
+    lg[2, 11, 3] = 0.0                                   # one finite logit: gap = +inf, the mean too
+    toks, msk, log, last = check_case(gpu, p, np.zeros((B, L), np.int32), masked, [lg, lg, lg], clear=False,
+                                      global_gap=[6.0, 3.0, 1.0])
+    assert (last["flags"] & 4).any()

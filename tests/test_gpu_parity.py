@@ -34,7 +34,9 @@ def gpu():
     return gpu_harness
 
 
-def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True, schedule=None, sample=False):
+def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True, schedule=None, sample=False,
+               global_gap=None):
+    """global_gap: optional function step -> threshold of the row-wide early-commit rule."""
     """Lock-step decode: oracle on the host (optionally on a subset of batch rows), library on
     the GPU over the whole batch; compares every step and the final state."""
     from gen.device import DeviceGenerator
@@ -57,14 +59,15 @@ def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True, s
         nt, frac = schedule(n) if schedule else (None, 0.0)
         frac = float(np.float32(frac))
         u = run.draw_uniforms(n) if sample else None
-        rec, T, R, rows = run.next_step(nt, frac, u)
+        gg = None if global_gap is None else float(np.float32(global_gap(n)))
+        rec, T, R, rows = run.next_step(nt, frac, u, gg)
         n_gpu = g.active_count()
         if use_device_gen:
             dgen.set_planted(T, R)
             dgen.fill(logits, n, J.jot_active_list(g.h), n_gpu)
         else:
             gpu.upload_rows(logits, act_full, rows, cfg.dtype)
-        g.step(logits, n_transfer=nt, transfer_frac=frac, uniforms=u)
+        g.step(logits, n_transfer=nt, transfer_frac=frac, uniforms=u, global_gap=gg)
         last = g.last()
         sel = followed[last["active"] // cfg.L] if batch_rows is not None else None
         gpu.compare_step(last, rec, act_full, TOL[cfg.dtype], sel)
@@ -315,3 +318,25 @@ def test_config5_full_size_repeats_bit_for_bit(gpu):
     for x, y in zip(a[1:], b[1:]):
         np.testing.assert_array_equal(x, y)
     assert a[2].shape[0] > 3 * cfg.B * 4
+
+
+# --------------------------------------------------------------------------- row-wide early commit
+
+def test_config2_with_rowwide_rule_staged_thresholds(gpu):
+    # thresholds falling with progress (7.5, 5, 2.5 on the logit scale, the values Section 6.1
+    # quotes for the global rule), early exit on top
+    cfg = CONFIGS[2].replace(steps=36, L=64 + 128, conf_mode=CONF_RATIO, tau_max=90.0, tau_min=1.0)
+    stage = lambda n: 7.5 if n <= 12 else (5.0 if n <= 24 else 2.5)
+    n = run_parity(gpu, cfg, global_gap=stage)
+    assert n <= cfg.steps + 16
+
+
+def test_config4_rowwide_rule_with_schedule_and_sampling(gpu):
+    cfg = CONFIGS[4].replace(B=4, L=128 + 96, steps=96)
+    run_parity(gpu, cfg, batch_rows=[0, 3], sample=True, global_gap=lambda n: 6.0,
+               schedule=lambda n: (np.ones(cfg.B, np.int32), 0.0))
+
+
+def test_config5_rowwide_rule_short(gpu):
+    cfg = CONFIGS[5].replace(B=3, steps=40, conv="mixture")
+    run_parity(gpu, cfg, batch_rows=[0, 2], max_steps=40, global_gap=lambda n: 3.0)
