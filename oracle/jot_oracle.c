@@ -150,3 +150,30 @@ int32_t jot_oracle_sample_row(const void *row, int dtype, int32_t V, double u,
     *cdf_above = cum;
     return last;
 }
+
+/*
+ * Stability signal between consecutive steps (the per-token rule Section 2 attributes to KLASS:
+ * the KL divergence between the distributions of consecutive steps identifies stable
+ * predictions).  D( pi_now || pi_prev ) = sum_v pi_now(v) * ( log pi_now(v) - log pi_prev(v) ),
+ * with 0 * log 0 = 0, and +inf if pi_prev(v) = 0 < pi_now(v) for some v.
+ * Returns NaN if either row has no softmax.
+ */
+double jot_oracle_kl_row(const void *row_now, const void *row_prev, int dtype, int32_t V)
+{
+    int32_t a;
+    double m1, m2, S, pm1, pm2, pS;
+    if (row_stats(row_now, dtype, V, &a, &m1, &m2, &S) || row_stats(row_prev, dtype, V, &a, &pm1, &pm2, &pS))
+        return NAN;
+    const double lse = m1 + log(S), plse = pm1 + log(pS);
+    double kl = 0.0;
+    for (int32_t v = 0; v < V; v++) {
+        const double x = widen(row_now, dtype, v), y = widen(row_prev, dtype, v);
+        const double pv = exp(x - m1) / S;
+        if (pv > 0.0) {
+            if (y == -INFINITY)
+                return INFINITY;
+            kl += pv * ((x - lse) - (y - plse));
+        }
+    }
+    return kl;
+}

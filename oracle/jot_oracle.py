@@ -43,6 +43,13 @@ row, g_b = mean over the row's examined positions that have a softmax of the top
 m1 - m2; if g_b >= global_gap (a threshold the caller passes for this step, so a staged
 threshold is the caller's schedule) every such position of the row is finalized this step.
 
+Stability rule (the per-token rule Section 2 attributes to KLASS: the KL divergence between the
+distributions of consecutive steps identifies predictions that have stopped moving; Section 6.1
+quotes its two thresholds, tau_KL and tau_conf).  Here: an examined position is stable at step n
+if it was examined, with a softmax, at step n - 1 too, D(pi_n || pi_{n-1}) <= kl_threshold and
+p1 >= kl_min_prob; stable positions are finalized, OR-ed with the other rules.  pi_{n-1} comes from
+the previous step's logits, which the caller keeps and passes.
+
 Besides the paper's ratio r, two other confidence signals computed from the same
 (p1, p2) are selectable, because the workloads this is tested on quote
 thresholds on the probability scale: p1 itself, and the gap p1 - p2.
@@ -92,6 +99,8 @@ def _load():
         lib.jot_oracle_sample_row.argtypes = [
             ctypes.c_void_p, ctypes.c_int, ctypes.c_int32, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p]
         lib.jot_oracle_sample_row.restype = ctypes.c_int32
+        lib.jot_oracle_kl_row.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int32]
+        lib.jot_oracle_kl_row.restype = ctypes.c_double
         _lib = lib
     return _lib
 
@@ -137,6 +146,13 @@ def sample_row(row: np.ndarray, dtype: int, u: float):
     v = _load().jot_oracle_sample_row(row.ctypes.data, dtype, row.shape[1], float(u),
                                       ctypes.byref(lo), ctypes.byref(hi))
     return int(v), lo.value, hi.value
+
+
+def kl_row(row_now: np.ndarray, row_prev: np.ndarray, dtype: int) -> float:
+    """D(pi_now || pi_prev) of two logit rows in double (NaN if either has no softmax)."""
+    a = _check_rows(row_now.reshape(1, -1), dtype)
+    b = _check_rows(row_prev.reshape(1, -1), dtype)
+    return float(_load().jot_oracle_kl_row(a.ctypes.data, b.ctypes.data, dtype, a.shape[1]))
 
 
 @dataclass
@@ -229,6 +245,8 @@ class StepRecord:
     sched: np.ndarray = None    # [A] bool: picked by the transfer schedule
     k_row: np.ndarray = None    # [B] number of positions the schedule picked per batch row
     final_token: np.ndarray = None  # [A] token written if finalized: argmax, or the sample
+    stable: np.ndarray = None       # [A] bool: finalized by the KL stability rule
+    kl: np.ndarray = None           # [A] D(pi_n || pi_{n-1}); nan where there is no previous distribution
     rowwide: np.ndarray = None      # [A] bool: finalized by the row-wide gap rule
     gap_row: np.ndarray = None      # [B] mean top-2 logit gap of the row's examined positions (nan: none)
     cdf_margin: np.ndarray = None   # [A] with sampling: distance of u from the nearer edge of the
@@ -244,6 +262,7 @@ class OracleState:
     commit_log: list = field(default_factory=list)   # (step, b*L+i, token)
     anomalies: int = 0
     threads: int = 1
+    last_ok_step: np.ndarray = None   # [B, L] last step at which the position was examined with a softmax
 
     @classmethod
     def init(cls, params: OracleParams, tokens: np.ndarray, masked: np.ndarray, threads: int = 1):
@@ -252,7 +271,8 @@ class OracleState:
             raise ValueError("tokens/masked must be [B, L]")
         if p.V < 2 or p.D < 0 or not (0.0 < p.gamma <= 1.0) or p.tau_min > p.tau_max:
             raise ValueError("invalid parameters")
-        return cls(p, tokens.astype(np.int32).copy(), masked.astype(bool).copy(), threads=threads)
+        return cls(p, tokens.astype(np.int32).copy(), masked.astype(bool).copy(), threads=threads,
+                   last_ok_step=np.full((p.B, p.L), -1, np.int64))
 
     def active_list(self) -> np.ndarray:
         """Ascending flattened indices b*L+i of the positions the next step examines."""
@@ -262,13 +282,16 @@ class OracleState:
         return int(self.active_list().size)
 
     def evaluate(self, rows: np.ndarray, n_transfer=None, transfer_frac: float = 0.0,
-                 sample_u=None, global_gap=None) -> StepRecord:
+                 sample_u=None, global_gap=None, prev_rows=None, kl_threshold=None,
+                 kl_min_prob: float = 0.0) -> StepRecord:
         """Decisions of the next step for the given logit rows (rows[k] belongs to
         active_list()[k]) WITHOUT changing the state.  n_transfer ([B] ints) and transfer_frac
         describe the transfer schedule of this step; by default it reveals nothing.
         sample_u: optional [B, L] uniform numbers in [0, 1); when given, a finalized position
         takes a token sampled from pi (inverse CDF at sample_u[b, i]) instead of the argmax.
-        global_gap: optional threshold of the row-wide early-commit rule for this step."""
+        global_gap: optional threshold of the row-wide early-commit rule for this step.
+        prev_rows / kl_threshold / kl_min_prob: the stability rule; prev_rows[k] is the previous
+        step's logit row of active_list()[k]."""
         p = self.params
         act = self.active_list()
         if rows.shape[0] != act.size:
@@ -287,7 +310,8 @@ class OracleState:
             exit_ = ok & (conf >= tau)                          # Eq. 6
         sched, k_row = self._schedule(act, p1, ok, n_transfer, transfer_frac)
         rowwide, gap_row = self._rowwide(act, m1, m2, ok, global_gap)
-        commit = exit_ | sched | rowwide                        # logical OR, uncapped
+        stable, kl = self._stable(act, rows, prev_rows, p1, ok, kl_threshold, kl_min_prob)
+        commit = exit_ | sched | rowwide | stable               # logical OR, uncapped
         final = a.copy()
         margin = np.full(act.size, np.inf)
         if sample_u is not None:
@@ -298,7 +322,21 @@ class OracleState:
                 final[k] = v
                 margin[k] = min(u - lo, hi - u)
         return StepRecord(self.step_index + 1, act, a, p1, p2, conf, tau, phi, commit, st,
-                          exit_, sched, k_row, final, rowwide, gap_row, margin)
+                          exit_, sched, k_row, final, stable, kl, rowwide, gap_row, margin)
+
+    def _stable(self, act, rows, prev_rows, p1, ok, kl_threshold, kl_min_prob):
+        """KL stability rule; needs the position to have been examined, with a softmax, in the
+        step before."""
+        stable = np.zeros(act.size, bool)
+        kl = np.full(act.size, np.nan)
+        if kl_threshold is None:
+            return stable, kl
+        had_prev = self.last_ok_step.reshape(-1)[act] == self.step_index
+        for k in np.flatnonzero(ok & had_prev):
+            kl[k] = kl_row(rows[k], prev_rows[k], self.params.dtype)
+        with np.errstate(invalid="ignore"):
+            stable = ok & had_prev & (kl <= kl_threshold) & (p1 >= kl_min_prob)
+        return stable, kl
 
     def _rowwide(self, act, m1, m2, ok, global_gap):
         """Row-wide early commit: mean top-2 logit gap of a row's examined positions >= threshold
@@ -351,10 +389,12 @@ class OracleState:
             flat_msk[pos] = False
             self.commit_log.append((rec.step, pos, int(tok)))
         self.anomalies += int(rec.status.sum())
+        self.last_ok_step.reshape(-1)[rec.active[rec.status == 0]] = rec.step
 
     def step(self, rows: np.ndarray, n_transfer=None, transfer_frac: float = 0.0, sample_u=None,
-             global_gap=None) -> StepRecord:
-        rec = self.evaluate(rows, n_transfer, transfer_frac, sample_u, global_gap)
+             global_gap=None, prev_rows=None, kl_threshold=None, kl_min_prob: float = 0.0) -> StepRecord:
+        rec = self.evaluate(rows, n_transfer, transfer_frac, sample_u, global_gap, prev_rows, kl_threshold,
+                            kl_min_prob)
         self.apply(rec)
         return rec
 

@@ -13,6 +13,7 @@ import pytest
 import test_oracle_pins as P
 import test_oracle_rowwide_pins as R
 import test_oracle_schedule_pins as S
+import test_oracle_stability_pins as K
 from oracle import jot_oracle as O
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -53,6 +54,12 @@ def pin_battery():
         ("rowwide_inclusive", R.test_threshold_is_inclusive_and_off_by_default),
         ("rowwide_or", R.test_rows_without_softmax_neither_count_nor_commit_and_rule_is_ored),
         ("rowwide_blocks", R.test_block_mode_applies_the_rule_to_the_current_block_only),
+        ("kl_scipy", K.test_kl_matches_scipy_and_basic_properties),
+        ("kl_two_token", K.test_two_token_closed_form_and_infinities),
+        ("kl_rule", K.test_rule_needs_history_small_kl_and_enough_confidence),
+        ("kl_or", K.test_rule_is_ored_with_the_others_and_off_by_default),
+        ("kl_blocks", K.test_new_block_has_no_history),
+        ("kl_history", K.test_history_means_the_step_just_before),
     ]
     return b
 
@@ -142,9 +149,9 @@ def test_python_level_mistake_is_caught(name, monkeypatch):
 def test_sequential_update_is_caught(monkeypatch):
     orig = O.OracleState.evaluate
 
-    def evaluate_sequential(self, rows, n_transfer=None, transfer_frac=0.0, sample_u=None, global_gap=None):
+    def evaluate_sequential(self, rows, *a, **kw):
         # decide positions one at a time, each seeing the commits made before it in the same step
-        rec = orig(self, rows, n_transfer, transfer_frac, sample_u, global_gap)
+        rec = orig(self, rows, *a, **kw)
         masked = self.masked.copy()
         flat = masked.reshape(-1)
         for k in range(rec.active.size):
@@ -238,11 +245,39 @@ def test_rowwide_mistake_is_caught(kind, monkeypatch):
     assert failing_pins(), f"no pin notices: {kind}"
 
 
+def _stable_variant(kind):
+    def _stable(self, act, rows, prev_rows, p1, ok, kl_threshold, kl_min_prob):
+        stable = np.zeros(act.size, bool)
+        kl = np.full(act.size, np.nan)
+        if kl_threshold is None:
+            return stable, kl
+        had_prev = self.last_ok_step.reshape(-1)[act] == self.step_index
+        if kind == "no_history_needed":
+            had_prev = np.ones(act.size, bool)
+        if kind == "any_earlier_step_counts_as_history":
+            had_prev = self.last_ok_step.reshape(-1)[act] >= 0
+        for k in np.flatnonzero(ok & had_prev):
+            kl[k] = O.kl_row(rows[k], prev_rows[k], self.params.dtype)
+        with np.errstate(invalid="ignore"):
+            small = kl < kl_threshold if kind == "strict_comparison" else kl <= kl_threshold
+            sure = np.ones(act.size, bool) if kind == "confidence_not_checked" else p1 >= kl_min_prob
+            stable = ok & had_prev & small & sure
+        return stable, kl
+    return _stable
+
+
+@pytest.mark.parametrize("kind", ["no_history_needed", "any_earlier_step_counts_as_history", "strict_comparison",
+                                  "confidence_not_checked"])
+def test_stability_mistake_is_caught(kind, monkeypatch):
+    monkeypatch.setattr(O.OracleState, "_stable", _stable_variant(kind))
+    assert failing_pins(), f"no pin notices: {kind}"
+
+
 def test_and_instead_of_or_is_caught(monkeypatch):
     orig = O.OracleState.evaluate
 
-    def evaluate_and(self, rows, n_transfer=None, transfer_frac=0.0, sample_u=None, global_gap=None):
-        rec = orig(self, rows, n_transfer, transfer_frac, sample_u, global_gap)
+    def evaluate_and(self, rows, n_transfer=None, transfer_frac=0.0, *a, **kw):
+        rec = orig(self, rows, n_transfer, transfer_frac, *a, **kw)
         if n_transfer is not None or transfer_frac:
             rec.commit = rec.exit & rec.sched
         return rec
@@ -259,6 +294,9 @@ C_MUTATIONS = {
     "no_max_subtraction": (r"sum \+= exp\(widen\(row, dtype, v\) - best\);", "sum += exp(widen(row, dtype, v));"),
     "sum_skips_last_entry": (r"for \(int32_t v = 0; v < V; v\+\+\)\n        sum \+=", "for (int32_t v = 0; v < V - 1; v++)\n        sum +="),
     "bf16_shift": (r"<< 16;", "<< 15;"),
+    "kl_reversed": (r"kl \+= pv \* \(\(x - lse\) - \(y - plse\)\);", "kl += pv * ((y - plse) - (x - lse));"),
+    "kl_without_normalizers": (r"kl \+= pv \* \(\(x - lse\) - \(y - plse\)\);", "kl += pv * (x - y);"),
+    "kl_weighted_by_previous": (r"const double pv = exp\(x - m1\) / S;", "const double pv = exp(y - pm1) / pS;"),
 }
 
 
@@ -273,7 +311,7 @@ def test_c_level_mistake_is_caught(name, monkeypatch, tmp_path):
     subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", str(lib), str(cfile), "-lm"])
     good = O._load()
     mut = ctypes.CDLL(str(lib))
-    for fn in ("jot_oracle_row_stats", "jot_oracle_softmax_row"):
+    for fn in ("jot_oracle_row_stats", "jot_oracle_softmax_row", "jot_oracle_sample_row", "jot_oracle_kl_row"):
         getattr(mut, fn).argtypes = getattr(good, fn).argtypes
         getattr(mut, fn).restype = getattr(good, fn).restype
     monkeypatch.setattr(O, "_lib", mut)
