@@ -150,6 +150,9 @@ def main():
                     help="sampling-based finalization (jot_step_sampled with uniform numbers drawn beforehand)")
     ap.add_argument("--graph", action="store_true",
                     help="capture each step's launches into a HIP graph once and replay them in the timed loop")
+    ap.add_argument("--kl", type=float, default=None, metavar="TAU_KL",
+                    help="also apply the KL stability rule with this threshold (the reduction then streams the "
+                         "previous step's logits too; steps must fit the resident buffers)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="N",
@@ -203,9 +206,23 @@ def main():
             dgen.fill(bufs[k], first_step + k, J.jot_active_list(g.h), n_act)
         torch.cuda.synchronize()
 
+    if args.kl is not None and (max(K, W) > resident or resident < 2):
+        raise SystemExit("--kl needs every step's logits resident, and at least two steps: change --steps / --warmup")
+
     def enqueue_step(g, k, step_no, st):
         frac = 1.0 / max(1, cfg.steps - step_no + 1) if args.schedule == "linear" else 0.0
-        if args.sample:
+        if args.kl is not None:
+            opt = J.JotStepOptions()
+            opt.transfer_frac = frac
+            if args.sample:
+                opt.uniforms_dev = uniforms[k].data_ptr()
+            opt.enable_kl = 1
+            # step 1 has no history, its previous-step operand is never used for a decision: hand it a
+            # buffer other than its own, so that the two streams do not share cache lines
+            opt.prev_logits_dev = bufs[k - 1 if k > 0 else resident - 1].data_ptr()
+            opt.kl_threshold, opt.kl_min_prob = args.kl, 0.0
+            J.jot_step_ex(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, opt, st)
+        elif args.sample:
             J.jot_step_sampled(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, 0, frac, uniforms[k].data_ptr(), st)
         elif args.schedule == "linear":
             J.jot_step_scheduled(g.h, bufs[k].data_ptr(), cfg.L * cfg.V, cfg.V, 0, frac, st)
@@ -265,6 +282,8 @@ def main():
     elems = float(sum(examined)) * cfg.V
     value = elems / seconds
     k_bytes = elems * esz / K                       # algorithmic bytes per launch (average)
+    if args.kl is not None:
+        k_bytes *= 2.0                              # the same rows of the previous step's logits as well
     if not kms:                                     # --graph: no events inside the graph; whole-step time instead
         kms = [seconds / K * 1e3] * K
     k_sec = sum(kms) * 1e-3 / K                     # average launch duration
@@ -278,13 +297,13 @@ def main():
         "config": {"workload": f"{cfg.name}: B={cfg.B}, L={cfg.L} ({cfg.gen_start} prompt + {cfg.n_gen} generated), "
                                f"V={cfg.V}, decode steps 1..{K}", "examined_positions_per_step": examined,
                    "conf_mode": cfg.conf_mode, "tau_max": cfg.tau_max, "tau_min": cfg.tau_min,
-                   "gamma": cfg.gamma, "D": cfg.D, "block_size": cfg.block_size, "schedule": args.schedule, "sampled_tokens": bool(args.sample), "hip_graph": bool(args.graph),
+                   "gamma": cfg.gamma, "D": cfg.D, "block_size": cfg.block_size, "schedule": args.schedule, "sampled_tokens": bool(args.sample), "hip_graph": bool(args.graph), "kl_threshold": args.kl,
                    "resident_logit_buffers": resident, "still_active_after": remaining, "anomalies": anomalies},
-        "hbm_GBps_active_logits": elems * esz / seconds / 1e9,
-        "pct_of_hbm_peak": 100.0 * elems * esz / seconds / 1e9 / HBM_PEAK_GBPS,
-        "roofline": {"bound": "hbm", "kernel": "jot_vocab_reduce_kernel", "achieved": achieved,
+        "hbm_GBps_active_logits": k_bytes * K / seconds / 1e9,
+        "pct_of_hbm_peak": 100.0 * k_bytes * K / seconds / 1e9 / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "jot_vocab_reduce_kl_kernel" if args.kl is not None else "jot_vocab_reduce_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": measured_traffic(args.config, K) if args.dtype is None and args.schedule == "none" and not args.sample and not args.graph else None, "bytes_per_launch": k_bytes, "avg_launch_ms": k_sec * 1e3,
+                     "traffic": measured_traffic(args.config, K) if args.dtype is None and args.schedule == "none" and not args.sample and not args.graph and args.kl is None else None, "bytes_per_launch": k_bytes, "avg_launch_ms": k_sec * 1e3,
                      "launch_ms": kms},
     }
     if not args.no_ceiling:

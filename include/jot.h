@@ -162,6 +162,21 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
  * those positions are finalized this step (argmax, or sampled if uniforms_dev is given), OR-ed
  * with the early exit and the schedule.  A staged threshold (e.g. 7.5 / 5 / 2.5 as decoding
  * progresses) is simply a different global_gap per call.
+ *
+ * KL stability rule (enable_kl != 0): the per-token rule the related-work section describes for
+ * KLASS -- the KL divergence between the distributions of consecutive steps marks predictions
+ * that have stopped moving (Section 6.1 quotes its two thresholds).  An examined position is
+ * stable if the previous step examined it too (and it had a softmax there),
+ * D(pi_now || pi_prev) <= kl_threshold, and p1 >= kl_min_prob; stable positions are finalized,
+ * OR-ed with the other rules.  The step then streams two logit tensors:
+ *   prev_logits_dev : the tensor that was `logits_dev` of the PREVIOUS step of this state, kept
+ *                     alive and unchanged by the caller (ping-pong two buffers); same element
+ *                     type, strides and alignment as logits_dev.  Its log-normalizers were stored
+ *                     by that step; passing anything else gives meaningless divergences.
+ * On the first step, and for positions the previous step did not examine (a block that has just
+ * become current), there is no previous distribution and the rule does not fire.  Vocabulary
+ * entries whose probability underflows binary32 relative to the row maximum (below ~1e-38) count
+ * as probability 0 in the divergence.
  */
 typedef struct {
     const int32_t* n_transfer_dev;   /* transfer schedule, see jot_step_scheduled; may be NULL      */
@@ -169,6 +184,10 @@ typedef struct {
     const float*   uniforms_dev;     /* sampling, see jot_step_sampled; NULL = argmax               */
     int32_t        enable_global_gap;/* != 0: apply the row-wide early-commit rule this step        */
     float          global_gap;       /* its threshold (finite)                                      */
+    int32_t        enable_kl;        /* != 0: apply the KL stability rule this step                 */
+    const void*    prev_logits_dev;  /* the previous step's logits (required if enable_kl)          */
+    float          kl_threshold;     /* tau_KL >= 0                                                 */
+    float          kl_min_prob;      /* tau_conf in [0, 1]                                          */
 } jot_step_options;
 
 int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
@@ -211,8 +230,11 @@ const float*   jot_last_p1(const jot_state* s);
 const float*   jot_last_p2(const jot_state* s);
 const float*   jot_last_tau(const jot_state* s);
 /* per examined position: bit 0 = passed Eq. 6, bit 1 = picked by the transfer schedule,
- * bit 2 = finalized by the row-wide early-commit rule */
+ * bit 2 = finalized by the row-wide early-commit rule, bit 3 = stable under the KL rule */
 const uint8_t* jot_last_flags(const jot_state* s);
+/* per examined position: D(pi_now || pi_prev) of a step run with enable_kl; NaN where the position
+ * has no previous distribution or no softmax, and after steps run without the rule */
+const float*   jot_last_kl(const jot_state* s);
 
 /*
  * Optional timing of the vocabulary-reduction kernel (the one that reads the logits):

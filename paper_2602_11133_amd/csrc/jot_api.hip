@@ -16,6 +16,7 @@
 #include "jot_sample.h"
 #include "jot_schedule.h"
 #include "jot_vocab_reduce.h"
+#include "jot_vocab_reduce_kl.h"
 
 namespace {
 
@@ -33,7 +34,7 @@ constexpr int kPerRowStepMax = 2048;   // longest per-row examined list handled 
 
 struct Layout {
     int64_t tokens, masked, commit_step, resolved_bits, active0, active1, counters, epoch, anomalies,
-        partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, last_m1, last_gap, last_final, sample_list, sample_count, row_block, row_n_active0, row_n_active1,
+        partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, last_m1, last_gap, last_final, lse, lse_step, last_kl, sample_list, sample_count, row_block, row_n_active0, row_n_active1,
         row_n_commit, commit_log, total;
     int64_t n_partials;
     int32_t words_per_row;
@@ -85,6 +86,9 @@ Layout make_layout(const jot_params* p, int target_items)
     l.last_m1 = take(n * 4);
     l.last_gap = take(n * 4);
     l.last_final = take(n * 4);
+    l.lse = take(n * 8);
+    l.lse_step = take(n * 4);
+    l.last_kl = take(n * 4);
     l.sample_list = take(n * 4);
     l.sample_count = take(4);
     l.row_block = take((int64_t)p->B * 4);
@@ -109,6 +113,7 @@ struct jot_state {
     bool sync_device;           // the last step was enqueued under stream capture: wait = device sync
     int32_t step;
     int grid_reduce;
+    int grid_reduce_kl, target_items_kl;
     int grid_sample;
     int target_items;
     JotDecideParams decide;
@@ -228,6 +233,17 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
         if (v >= 1 && v <= kMaxWgPerCu) occ = v;
     }
     s->grid_reduce = cus * occ;
+    {   // the reduction with the stability term has its own register footprint, hence its own grid
+        int occ_kl = 0;
+        const void* kfn_kl = p->dtype == JOT_F32 ? reinterpret_cast<const void*>(jot_vocab_reduce_kl_kernel<JotF32KL>)
+                                                 : reinterpret_cast<const void*>(jot_vocab_reduce_kl_kernel<JotBF16KL>);
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_kl, kfn_kl, reduce_wg, 0) != hipSuccess || occ_kl < 1)
+            occ_kl = kDefaultWgPerCu;
+        if (occ_kl > kMaxWgPerCu) occ_kl = kMaxWgPerCu;
+        s->grid_reduce_kl = cus * occ_kl;
+        s->target_items_kl = s->grid_reduce_kl * kItemsPerWg;
+        if (s->target_items_kl > max_target_items()) s->target_items_kl = max_target_items();
+    }
     s->grid_sample = cus * 4;
     s->target_items = s->grid_reduce * kItemsPerWg;
     if (s->target_items > max_target_items()) s->target_items = max_target_items();
@@ -288,7 +304,8 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
     hipLaunchKernelGGL(jot_init_copy_kernel, dim3((unsigned)((n + JOT_WG - 1) / JOT_WG)), dim3(JOT_WG), 0, st,
                        n, tokens_dev, masked_dev, s->at<int32_t>(s->lay.tokens),
                        s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
-                       s->counters(0), s->at<unsigned long long>(s->lay.anomalies), s->frame.epoch);
+                       s->counters(0), s->at<unsigned long long>(s->lay.anomalies), s->frame.epoch,
+                       s->at<int32_t>(s->lay.lse_step));
     int rc2 = (hipGetLastError() == hipSuccess) ? enqueue_compaction(s, /*creating=*/true, st, true) : JOT_ERR_HIP;
     if (rc2 == JOT_OK && hipStreamSynchronize(st) != hipSuccess) rc2 = JOT_ERR_HIP;
     if (rc2 != JOT_OK) {
@@ -332,7 +349,14 @@ int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t 
     const float transfer_frac = opt->transfer_frac;
     const float* uniforms_dev = opt->uniforms_dev;
     const bool do_rowwide = opt->enable_global_gap != 0;
+    const bool do_kl = opt->enable_kl != 0;
     if (!s || !logits_dev) return JOT_ERR_NULL_POINTER;
+    if (do_kl) {
+        if (!opt->prev_logits_dev) return JOT_ERR_NULL_POINTER;
+        if (reinterpret_cast<uintptr_t>(opt->prev_logits_dev) % 16) return JOT_ERR_MISALIGNED;
+        if (!(opt->kl_threshold >= 0.0f) || !isfinite(opt->kl_threshold)) return JOT_ERR_INVALID_ARG;
+        if (!(opt->kl_min_prob >= 0.0f && opt->kl_min_prob <= 1.0f)) return JOT_ERR_INVALID_ARG;
+    }
     if (do_rowwide && !isfinite(opt->global_gap)) return JOT_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(uniforms_dev) % 4) return JOT_ERR_MISALIGNED;
     int dev = -1;
@@ -359,7 +383,15 @@ int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t 
         s->prof_step[slot] = 0;
         if (hipEventRecord(s->prof0[slot], st) != hipSuccess) return JOT_ERR_HIP;
     }
-    if (p.dtype == JOT_F32)
+    if (do_kl && p.dtype == JOT_F32)
+        hipLaunchKernelGGL(jot_vocab_reduce_kl_kernel<JotF32KL>, dim3(s->grid_reduce_kl), dim3(JotF32KL::WG), 0, st,
+                           logits_dev, opt->prev_logits_dev, stride_b, stride_l, p.L, p.V, s->frame,
+                           s->at<JotPartial>(s->lay.partials), s->target_items_kl, INFINITY);
+    else if (do_kl)
+        hipLaunchKernelGGL(jot_vocab_reduce_kl_kernel<JotBF16KL>, dim3(s->grid_reduce_kl), dim3(JotBF16KL::WG), 0, st,
+                           logits_dev, opt->prev_logits_dev, stride_b, stride_l, p.L, p.V, s->frame,
+                           s->at<JotPartial>(s->lay.partials), s->target_items_kl, INFINITY);
+    else if (p.dtype == JOT_F32)
         hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotF32>, dim3(s->grid_reduce), dim3(JotF32::WG), 0, st,
                            logits_dev, stride_b, stride_l, p.L, p.V, s->frame,
                            s->at<JotPartial>(s->lay.partials), s->target_items, INFINITY);
@@ -391,6 +423,18 @@ int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t 
     dio.sample_list = uniforms_dev ? s->at<int32_t>(s->lay.sample_list) : nullptr;
     dio.sample_count = s->at<int32_t>(s->lay.sample_count);
     dio.anomalies = s->at<unsigned long long>(s->lay.anomalies);
+    dio.lse = s->at<double>(s->lay.lse);
+    dio.lse_step = s->at<int32_t>(s->lay.lse_step);
+    dio.last_kl = s->at<float>(s->lay.last_kl);
+    JotDecideParams dprm = s->decide;
+    if (do_kl) {
+        dprm.do_kl = 1;
+        dprm.kl_threshold = opt->kl_threshold;
+        dprm.kl_min_prob = opt->kl_min_prob;
+        dprm.target_items = s->target_items_kl;
+        dprm.split_align = p.dtype == JOT_F32 ? JotF32KL::WG * JotF32KL::VEC * JotF32KL::UNROLL
+                                              : JotBF16KL::WG * JotBF16KL::VEC * JotBF16KL::UNROLL;
+    }
     const bool do_schedule = n_transfer_dev || transfer_frac > 0.0f;
     JotScheduleParams sprm;
     sprm.B = p.B; sprm.L = p.L; sprm.transfer_frac = transfer_frac;
@@ -411,13 +455,13 @@ int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t 
     sio.sample_count = dio.sample_count;
 
     if (s->per_row_step) {
-        hipLaunchKernelGGL(jot_row_step_kernel, dim3(p.B), dim3(JOT_WG), 0, st, s->decide, dio, sprm, sio,
+        hipLaunchKernelGGL(jot_row_step_kernel, dim3(p.B), dim3(JOT_WG), 0, st, dprm, dio, sprm, sio,
                            s->compact, s->frame, s->at<uint8_t>(s->lay.masked),
                            s->at<int32_t>(s->lay.row_block), s->at<int32_t>(s->lay.row_n_commit));
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     } else {
         hipLaunchKernelGGL(jot_decide_kernel, dim3((unsigned)((n + JOT_WG - 1) / JOT_WG)), dim3(JOT_WG), 0, st,
-                           s->decide, dio, s->frame);
+                           dprm, dio, s->frame);
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
         if (do_schedule || do_rowwide) {
             hipLaunchKernelGGL(jot_row_rules_kernel, dim3(p.B), dim3(JOT_WG), 0, st, sprm, sio, s->frame);
@@ -486,6 +530,7 @@ const float* jot_last_p1(const jot_state* s) { return s ? s->at<float>(s->lay.la
 const float* jot_last_p2(const jot_state* s) { return s ? s->at<float>(s->lay.last_p2) : nullptr; }
 const float* jot_last_tau(const jot_state* s) { return s ? s->at<float>(s->lay.last_tau) : nullptr; }
 const uint8_t* jot_last_flags(const jot_state* s) { return s ? s->at<uint8_t>(s->lay.last_flags) : nullptr; }
+const float* jot_last_kl(const jot_state* s) { return s ? s->at<float>(s->lay.last_kl) : nullptr; }
 
 int jot_profile_enable(jot_state* s, int on)
 {

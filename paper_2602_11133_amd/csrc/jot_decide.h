@@ -7,6 +7,7 @@
 // kernels afterwards, so every thread of this kernel sees the mask as it was when the step began.
 #pragma once
 #include "jot_device.h"
+#include "jot_stability.h"
 
 // Arrays the decision writes or reads, all in the caller's workspace.
 struct JotDecideIO {
@@ -27,6 +28,9 @@ struct JotDecideIO {
     int32_t* sample_list;       // NULL unless this step samples its tokens
     int32_t* sample_count;
     unsigned long long* anomalies;
+    double* lse;                // per POSITION: log-normalizer m1 + ln S of the last step that examined it
+    int32_t* lse_step;          // per position: that step's number, -1 if it had no softmax there
+    float* last_kl;             // D(pi_now || pi_prev) per examined entry, NaN where undefined
 };
 
 struct JotDecideParams {
@@ -38,6 +42,9 @@ struct JotDecideParams {
     int32_t words_per_row;        // 64-bit words of the resolved-bit image per batch row
     int32_t target_items;
     int32_t split_align;          // piece alignment of the vocabulary reduction (elements)
+    int32_t do_kl;                // KL stability rule on this step (the partials then carry the cross term)
+    float kl_threshold;           // stable iff D(pi_now || pi_prev) <= kl_threshold ...
+    float kl_min_prob;            // ... and p1 >= kl_min_prob
     float gpow[JOT_MAX_D + 1];    // gpow[d] = gamma^d
 };
 
@@ -47,10 +54,10 @@ __device__ __forceinline__ void jot_decide_one(const JotDecideParams& prm, const
 {
     // ---- merge the pieces of the row, in piece order
     const JotPartial* q = io.partials + r * pieces;
-    float m1 = q[0].m1, m2 = q[0].m2, M = q[0].M, s = q[0].s;
+    float m1 = q[0].m1, m2 = q[0].m2, M = q[0].M, s = q[0].s, cross = q[0].pad[0];
     int32_t idx = q[0].idx;
     for (int j = 1; j < pieces; ++j)
-        jot_merge(m1, idx, m2, M, s, q[j].m1, q[j].idx, q[j].m2, q[j].M, q[j].s);
+        jot_merge_kl(m1, idx, m2, M, s, cross, q[j].m1, q[j].idx, q[j].m2, q[j].M, q[j].s, q[j].pad[0]);
 
     if (m1 == -INFINITY)
         idx = 0;            // every logit is -inf: all are equal, the smallest index is 0
@@ -94,7 +101,24 @@ __device__ __forceinline__ void jot_decide_one(const JotDecideParams& prm, const
     }
     const float tau = prm.tau_max - (prm.tau_max - prm.tau_min) * phi;   // Eq. 5
 
-    const bool commit = has_softmax && (conf >= tau);           // Eq. 6
+    const bool exit_now = has_softmax && (conf >= tau);         // Eq. 6
+
+    // ---- KL stability rule: needs the log-normalizer this position had in the step just before.
+    // D(pi || pi') = A/S - (m1 + ln S) + (m1' + ln S'); A and s share their scaling, so A/S = cross/s.
+    const double nan64 = __longlong_as_double(0x7ff8000000000000ll);
+    const double lse = has_softmax ? (double)m1 + log((double)S) : nan64;
+    bool stable = false;
+    float kl_out = __uint_as_float(0x7fc00000u);
+    if (prm.do_kl && has_softmax && io.lse_step[pos] == step - 1) {
+        const double kl = (double)cross / (double)s - lse + io.lse[pos];
+        kl_out = (float)kl;
+        stable = (kl <= (double)prm.kl_threshold) && (p1 >= prm.kl_min_prob);
+    }
+    io.lse[pos] = lse;
+    io.lse_step[pos] = has_softmax ? step : -1;
+    io.last_kl[r] = kl_out;
+
+    const bool commit = exit_now || stable;
     if (commit) {
         io.tokens[pos] = idx;
         io.commit_step[pos] = step;
@@ -107,7 +131,7 @@ __device__ __forceinline__ void jot_decide_one(const JotDecideParams& prm, const
     io.last_final[r] = idx;            // the sampling kernel, if it runs, overwrites this
     io.last_m1[r] = m1;
     io.last_gap[r] = m1 - m2;
-    io.last_flags[r] = commit ? 1 : 0;
+    io.last_flags[r] = (exit_now ? 1 : 0) | (stable ? 8 : 0);
     io.last_conf[r] = has_softmax ? conf : __uint_as_float(0x7fc00000u);
     io.last_p1[r] = p1;
     io.last_p2[r] = p2;

@@ -44,10 +44,12 @@ class GpuJot:
             pass
 
     def step(self, logits: torch.Tensor, stride_b=None, stride_l=None, n_transfer=None, transfer_frac=0.0,
-             uniforms=None, global_gap=None):
+             uniforms=None, global_gap=None, kl=None, prev_logits=None):
+        """kl = (kl_threshold, kl_min_prob) turns the KL stability rule on; prev_logits is then the
+        tensor the previous step was given (same layout)."""
         sb = logits.stride(0) if stride_b is None else stride_b
         sl = logits.stride(1) if stride_l is None else stride_l
-        if global_gap is not None:                       # the general entry point
+        if global_gap is not None or kl is not None:     # the general entry point
             opt = J.JotStepOptions()
             if n_transfer is not None:
                 self._nt = torch.from_numpy(np.ascontiguousarray(n_transfer, np.int32)).to(self.dev)
@@ -56,8 +58,14 @@ class GpuJot:
             if uniforms is not None:
                 self._u = torch.from_numpy(np.ascontiguousarray(uniforms, np.float32)).to(self.dev)
                 opt.uniforms_dev = self._u.data_ptr()
-            opt.enable_global_gap = 1
-            opt.global_gap = global_gap
+            if global_gap is not None:
+                opt.enable_global_gap = 1
+                opt.global_gap = global_gap
+            if kl is not None:
+                assert prev_logits.stride() == logits.stride() and prev_logits.dtype == logits.dtype
+                opt.enable_kl = 1
+                opt.prev_logits_dev = prev_logits.data_ptr()
+                opt.kl_threshold, opt.kl_min_prob = kl
             J.jot_step_ex(self.h, logits.data_ptr(), sb, sl, opt, self.stream)
             return
         if uniforms is not None:
@@ -109,6 +117,7 @@ class GpuJot:
             out[name] = J.device_to_host(getattr(J, "jot_last_" + name)(self.h), n, np.float32)
         out["flags"] = J.device_to_host(J.jot_last_flags(self.h), n, np.uint8)
         out["final"] = J.device_to_host(J.jot_last_final_token(self.h), n, np.int32)
+        out["kl"] = J.device_to_host(J.jot_last_kl(self.h), n, np.float32)
         return out
 
 
@@ -130,6 +139,9 @@ def rel_err(got: np.ndarray, want: np.ndarray) -> np.ndarray:
         e = np.abs(got.astype(np.float64) - want) / np.abs(want)
     e[(got == want)] = 0.0
     return e
+
+
+KL_TOL = 1e-5         # absolute, on divergences of order 1 and below; relative above
 
 
 def compare_step(gpu_last: dict, rec, act_full: np.ndarray, tol: float, select=None):
@@ -159,5 +171,12 @@ def compare_step(gpu_last: dict, rec, act_full: np.ndarray, tol: float, select=N
     np.testing.assert_array_equal((g["flags"] & 2).astype(bool), want_sched)
     want_rowwide = rec.rowwide if rec.rowwide is not None else np.zeros_like(rec.commit)
     np.testing.assert_array_equal((g["flags"] & 4).astype(bool), want_rowwide)
+    want_stable = rec.stable if rec.stable is not None else np.zeros_like(rec.commit)
+    np.testing.assert_array_equal((g["flags"] & 8).astype(bool), want_stable)
+    if rec.kl is not None and np.isfinite(rec.kl).any():
+        fin = np.isfinite(rec.kl)
+        assert not np.isfinite(g["kl"][~fin]).any()              # no history / no softmax / infinite
+        err = np.abs(g["kl"][fin].astype(np.float64) - rec.kl[fin])
+        assert (err <= KL_TOL * np.maximum(1.0, np.abs(rec.kl[fin]))).all(), float(err.max())
     want_final = rec.final_token if rec.final_token is not None else rec.token
     np.testing.assert_array_equal(g["final"][rec.commit], want_final[rec.commit])   # bit exact

@@ -14,6 +14,7 @@ from oracle import jot_oracle as O
 GUARD = 1e-4          # |conf - tau| >= GUARD * max(1, |tau|) for every examined position
 GUARD_U = 1e-6        # sampling: the uniform number stays this far (in probability) from both
                       # edges of the chosen token's CDF interval
+GUARD_KL = 2e-5       # stability rule: |KL - tau_KL| >= GUARD_KL * max(1, tau_KL), |p1 - tau_conf| >= GUARD
 MAX_BUMPS = 200
 
 
@@ -23,13 +24,20 @@ def oracle_params(cfg: JotConfig) -> O.OracleParams:
                           eps=cfg.eps, gen_start=cfg.gen_start, block_size=cfg.block_size)
 
 
-def too_close(rec: O.StepRecord, L: int = 0) -> np.ndarray:
+def too_close(rec: O.StepRecord, L: int = 0, kl=None) -> np.ndarray:
     """Examined entries whose decision is not well posed: a confidence within the guard band of
     its threshold, or -- with a transfer schedule -- the last position the schedule takes in a
     row when the best position it leaves behind has nearly the same p1."""
     ok = rec.status == 0
     with np.errstate(invalid="ignore"):
         near = ok & (np.abs(rec.conf - rec.tau) < GUARD * np.maximum(1.0, np.abs(rec.tau)))
+    if kl is not None:
+        tau_kl, tau_conf = kl
+        with np.errstate(invalid="ignore"):
+            has = ok & np.isfinite(rec.kl)
+            near |= has & (np.abs(rec.kl - tau_kl) < GUARD_KL * max(1.0, tau_kl))
+            if tau_conf > 0.0:
+                near |= has & (rec.kl <= tau_kl) & (np.abs(rec.p1 - tau_conf) < GUARD)
     if rec.sched is not None and rec.sched.any():
         row_of = rec.active // L
         for b in np.unique(row_of[rec.sched]):
@@ -56,6 +64,8 @@ class LockstepRun:
         self.state = O.OracleState.init(oracle_params(sub), tokens[self.batch_rows],
                                         masked[self.batch_rows], threads=threads)
         self.n_bumps = 0
+        self.gen_prev = HostGenerator(cfg, self.traj.target, self.traj.rival, threads)
+        self.prev_tables = None          # final planted tables of the step before
 
     def to_full(self, sub_pos: np.ndarray) -> np.ndarray:
         L = self.cfg.L
@@ -70,13 +80,14 @@ class LockstepRun:
         rng = np.random.default_rng([self.cfg.seed, 0x756E6966, step])
         return rng.random((self.cfg.B, self.cfg.L), dtype=np.float32)
 
-    def next_step(self, n_transfer=None, transfer_frac: float = 0.0, sample_u=None, global_gap=None):
+    def next_step(self, n_transfer=None, transfer_frac: float = 0.0, sample_u=None, global_gap=None, kl=None):
         """Advance the oracle one step.  Returns (rec, T, R, rows) where rec.active is in
         sub-batch numbering, T/R are the final planted tables of this step (full canvas) and
         rows are the logit rows the oracle saw (a view valid until the next call).
         n_transfer ([B] of the FULL batch) / transfer_frac: the step's transfer schedule.
         sample_u ([B, L] float32 of the FULL batch, modified in place where a number has to be
-        redrawn to stay clear of a CDF edge): sampling-based finalization."""
+        redrawn to stay clear of a CDF edge): sampling-based finalization.
+        kl = (kl_threshold, kl_min_prob): the KL stability rule against the previous step's rows."""
         if n_transfer is not None:
             n_transfer = np.asarray(n_transfer)[self.batch_rows]
         st, tr = self.state, self.traj
@@ -86,9 +97,16 @@ class LockstepRun:
         rows = self.gen.rows(n, act_full, T, R)
         u_sub = None if sample_u is None else sample_u[self.batch_rows]
         redraw = np.random.default_rng([self.cfg.seed, 0x72656472, n])
-        rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub, global_gap)
+        kl_kw = {}
+        if kl is not None:
+            if self.prev_tables is None:
+                prev_rows = rows                  # first step: no position has a history, never read
+            else:
+                prev_rows = self.gen_prev.rows(n - 1, act_full, *self.prev_tables)
+            kl_kw = dict(prev_rows=prev_rows, kl_threshold=kl[0], kl_min_prob=kl[1])
+        rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub, global_gap, **kl_kw)
         for _ in range(MAX_BUMPS):
-            bad = too_close(rec, self.cfg.L)
+            bad = too_close(rec, self.cfg.L, kl)
             amount = {}                           # entry -> how much to raise its target logit (default 0.25)
             if global_gap is not None:            # a row's mean gap too close to the row-wide threshold:
                 scale = max(1.0, abs(global_gap))
@@ -106,7 +124,7 @@ class LockstepRun:
                         sample_u[bb, ii] = redraw.random(dtype=np.float32)
                     u_sub = sample_u[self.batch_rows]
                     if bad.size == 0:
-                        rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub, global_gap)
+                        rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub, global_gap, **kl_kw)
                         continue
             if bad.size == 0:
                 break
@@ -116,8 +134,9 @@ class LockstepRun:
             T, R = tr.planted(n)
             fixer = HostGenerator(self.cfg, tr.target, tr.rival, 1)
             rows[bad] = fixer.rows(n, act_full[bad], T, R)
-            rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub, global_gap)
+            rec = st.evaluate(rows, n_transfer, transfer_frac, u_sub, global_gap, **kl_kw)
         else:
             raise RuntimeError("could not clear the guard band")
         st.apply(rec)
+        self.prev_tables = (T, R)
         return rec, T, R, rows

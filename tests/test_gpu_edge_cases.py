@@ -10,7 +10,7 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 from gen.bf16 import bf16_bits_to_f32, f32_to_bf16_bits  # noqa: E402
-from harness import GUARD, GUARD_U, too_close  # noqa: E402
+from harness import GUARD, GUARD_KL, GUARD_U, too_close  # noqa: E402
 from oracle import jot_oracle as O  # noqa: E402
 
 
@@ -64,8 +64,9 @@ def to_device(logits: np.ndarray, dtype: int, stride_l: int):
 
 
 def check_case(gpu, p: O.OracleParams, tokens, masked, logit_seq, stride_pad=0, tol=None, clear=True,
-               schedule=None, uniforms=None, global_gap=None):
-    """schedule: optional list of (n_transfer, frac) per step.  uniforms: optional list of [B, L]
+               schedule=None, uniforms=None, global_gap=None, kl=None):
+    """kl: optional list, per step, of (kl_threshold, kl_min_prob) or None: the KL stability rule
+    against the logits of the step before.  schedule: optional list of (n_transfer, frac) per step.  uniforms: optional list of [B, L]
     float32 arrays per step (sampling-based finalization); numbers that fall within GUARD_U of
     an edge of the chosen token's CDF interval are redrawn here (they are inputs)."""
     import paper_2602_11133_amd as J
@@ -82,6 +83,7 @@ def check_case(gpu, p: O.OracleParams, tokens, masked, logit_seq, stride_pad=0, 
     g = gpu.GpuJot(jp, tokens, masked)
     tol = tol or (1e-5 if p.dtype == O.F32 else 2e-3)
     np.testing.assert_array_equal(g.active_list(), st.active_list().astype(np.int32))
+    prev_logits = prev_dev = None
     for n, logits in enumerate(logit_seq, 1):
         logits = np.array(logits, np.float32)
         if p.dtype == O.BF16:
@@ -105,12 +107,24 @@ def check_case(gpu, p: O.OracleParams, tokens, masked, logit_seq, stride_pad=0, 
                     break
                 for k in edge:
                     u.reshape(-1)[act[k]] = redraw.random(dtype=np.float32)
-        rec = st.step(as_rows(logits.reshape(p.B * p.L, p.V)[act], p.dtype), nt, frac, u, gg)
+        klo = kl[n - 1] if kl else None
+        kl_kw = {}
+        if klo is not None:
+            klo = (float(np.float32(klo[0])), float(np.float32(klo[1])))
+            before = logits if prev_logits is None else prev_logits
+            kl_kw = dict(prev_rows=as_rows(before.reshape(p.B * p.L, p.V)[act], p.dtype), kl_threshold=klo[0],
+                         kl_min_prob=klo[1])
+        rec = st.step(as_rows(logits.reshape(p.B * p.L, p.V)[act], p.dtype), nt, frac, u, gg, **kl_kw)
+        if klo is not None:
+            assert too_close(rec, p.L, klo).size == 0 or clear, "a divergence sits on its threshold"
+            fin = np.isfinite(rec.kl)
+            assert not np.any(np.abs(rec.kl[fin] - klo[0]) < GUARD_KL * max(1.0, klo[0])), "a divergence sits on its threshold"
         if gg is not None:
             assert np.all(~(np.abs(rec.gap_row - gg) < GUARD * max(1.0, abs(gg)))), "row mean sits on the threshold"
         dev = to_device(logits, p.dtype, stride_l)
         g.step(dev, stride_b=p.L * stride_l, stride_l=stride_l, n_transfer=nt, transfer_frac=frac, uniforms=u,
-               global_gap=gg)
+               global_gap=gg, kl=klo, prev_logits=dev if prev_dev is None else prev_dev)
+        prev_logits, prev_dev = logits, dev
         gpu.compare_step(g.last(), rec, act, tol)
         np.testing.assert_array_equal(g.tokens(), st.tokens)
         np.testing.assert_array_equal(g.masked(), st.masked)
@@ -502,3 +516,112 @@ def test_rowwide_rule(gpu, L, block):
     toks, msk, log, last = check_case(gpu, p, np.zeros((B, L), np.int32), masked, [lg, lg, lg], clear=False,
                                       global_gap=[6.0, 3.0, 1.0])
     assert (last["flags"] & 4).any()
+
+
+# --------------------------------------------------------------------------- KL stability rule
+
+def drifting_logits(rng, B, L, V, steps, scale=2.0, drift=0.05):
+    """A sequence of logit tensors whose rows move by small random amounts per step, a few rows by
+    large ones, around a planted token of varying strength."""
+    base = (rng.standard_normal((B, L, V)) * scale).astype(np.float32)
+    target = rng.integers(0, V, (B, L))
+    boost = rng.uniform(0.0, 12.0, (B, L)).astype(np.float32)
+    np.put_along_axis(base, target[..., None], boost[..., None], -1)
+    seq = []
+    for n in range(steps):
+        amount = np.where(rng.random((B, L, 1)) < 0.2, 1.0, drift).astype(np.float32)
+        base = base + (rng.standard_normal((B, L, V)).astype(np.float32) * amount)
+        seq.append(base.copy())
+    return seq
+
+
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+@pytest.mark.parametrize("V", [2, 9, 1003, 8200, 40_003])
+def test_stability_rule(gpu, dtype, V):
+    B, L = 3, 40
+    rng = np.random.default_rng(900 + V)
+    p = O.OracleParams(B=B, L=L, V=V, dtype=dtype, conf_mode=O.CONF_MAXPROB, tau_max=2.0, tau_min=2.0, D=4,
+                       gen_start=5)                       # the early exit never fires: only the rule under test
+    masked = np.zeros((B, L), bool)
+    masked[:, 5:] = rng.random((B, L - 5)) < 0.9
+    seq = drifting_logits(rng, B, L, V, 4, drift=0.05 if dtype == O.F32 else 0.25)
+    thr = 0.004 if dtype == O.F32 else 0.09
+    toks, msk, log, last = check_case(gpu, p, np.zeros((B, L), np.int32), masked, seq, clear=False, stride_pad=1,
+                                      kl=[(thr, 0.0), (thr, 0.3), None, (thr * 2, 0.0)])
+    assert len(log) > 0 and (msk.any() or V < 100)         # some positions were stable, some (long rows) were not
+
+
+def test_stability_rule_when_rows_are_cut_into_pieces(gpu):
+    B, L, V = 1, 7, 300_007
+    rng = np.random.default_rng(77)
+    p = O.OracleParams(B=B, L=L, V=V, dtype=O.F32, conf_mode=O.CONF_MAXPROB, tau_max=2.0, tau_min=2.0, D=2,
+                       gen_start=1)
+    masked = np.ones((B, L), bool)
+    masked[0, 0] = False
+    a = (rng.standard_normal((B, L, V)) * 2).astype(np.float32)
+    a[0, 1, 250_000] = 14.0                               # decided row, planted in a late piece
+    a[0, 2, 5] = 30.0                                     # very decided: the other pieces carry almost no weight
+    b = a + (rng.standard_normal((B, L, V)) * 0.02).astype(np.float32)
+    b[0, 3] = a[0, 3] + (rng.standard_normal(V) * 0.8).astype(np.float32)     # this one moved
+    b[0, 4, V - 3:] += 6.0                                # movement confined to the ragged tail
+    toks, msk, log, last = check_case(gpu, p, np.zeros((B, L), np.int32), masked, [a, b, b], clear=False,
+                                      kl=[(0.001, 0.0), (0.001, 0.0), (0.0005, 0.0)])
+    got = {int(pos): int(step) for step, pos, tok in log}
+    assert got[1] == 2 and got[2] == 2 and got[5] == 2 and got[6] == 2        # still within 0.001 of their past
+    assert got[3] == 3 and got[4] == 3                                         # identical rows: divergence 0
+    assert np.all(np.abs(last["kl"]) < 1e-5)               # (the rows are cut differently in the two steps)
+
+
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+def test_stability_rule_with_vocabulary_masks_and_broken_rows(gpu, dtype):
+    B, L, V = 2, 12, 520
+    rng = np.random.default_rng(31)
+    p = O.OracleParams(B=B, L=L, V=V, dtype=dtype, conf_mode=O.CONF_MAXPROB, tau_max=2.0, tau_min=2.0, D=2,
+                       gen_start=2, block_size=5)
+    masked = np.zeros((B, L), bool)
+    masked[:, 2:] = True
+    a = rng.standard_normal((B, L, V)).astype(np.float32)
+    a[:, :, 9] += 8.0
+    a[:, :, 100:200] = -np.inf                            # a static vocabulary mask, the same in every step
+    a[:, :, 300:310] = -1e30                              # ... and fill values
+    b = a.copy()
+    b[:, :, :100] += (rng.standard_normal((B, L, 100)) * 0.05).astype(np.float32)
+    b[0, 3, 150] = -20.0                                  # weight appears where there was none: divergence +inf
+    b[0, 4, 50] = np.nan                                  # no softmax now
+    a[1, 2, 7] = np.nan                                   # no softmax before
+    a[1, 3, 400] = np.inf                                 # no softmax before either
+    c = b.copy()
+    c[0, 4, 50] = 0.0                                     # mended, but its previous step had none
+    toks, msk, log, last = check_case(gpu, p, np.zeros((B, L), np.int32), masked, [a, b, c, c, c], clear=False,
+                                      kl=[(0.5, 0.5)] * 5)
+    assert len(log) > 0
+
+
+def test_stability_rule_argument_errors(gpu):
+    import paper_2602_11133_amd as J
+    p, tokens, masked, seq = random_case(64, B=2, L=20, V=100, gs=4, conf_mode=O.CONF_RATIO, tau_max=5.0,
+                                         tau_min=1.0, gamma=0.5, D=4, steps=1)
+    jp = J.JotParams(B=2, L=20, V=100, dtype=0, conf_mode=0, tau_max=5.0, tau_min=1.0, gamma=0.5, D=4,
+                     eps=1e-12, gen_start=4, block_size=0)
+    g = gpu.GpuJot(jp, tokens, masked)
+    dev = to_device(seq[0], O.F32, 100)
+    lib = J.load_library()
+
+    def call(**kw):
+        opt = J.JotStepOptions()
+        opt.enable_kl = 1
+        opt.prev_logits_dev = dev.data_ptr()
+        opt.kl_threshold, opt.kl_min_prob = 0.1, 0.5
+        for k, v in kw.items():
+            setattr(opt, k, v)
+        import ctypes
+        return lib.jot_step_ex(g.h, dev.data_ptr(), 2000, 100, ctypes.byref(opt), g.stream)
+
+    assert call(prev_logits_dev=None) == -2
+    assert call(prev_logits_dev=dev.data_ptr() + 4) == -5
+    assert call(kl_threshold=-0.1) == -1
+    assert call(kl_threshold=float("nan")) == -1
+    assert call(kl_min_prob=1.5) == -1
+    assert J.jot_step_index(g.h) == 0
+    assert call() == 0 and J.jot_step_index(g.h) == 1
+    g.close()

@@ -19,6 +19,10 @@ from harness import LockstepRun  # noqa: E402
 
 THREADS = int(os.environ.get("JOT_TEST_THREADS", "16"))
 TOL = {F32: 1e-5, BF16: 2e-3}
+# (kl_threshold, kl_min_prob) per workload, placed inside the bulk of the divergences the workload's
+# consecutive steps show (independent noise of variance ~1 per step: about 1; the low-noise
+# large-vocabulary workload: about 1.2e-3), so that the rule decides both ways
+KL_CASES = {2: (1.0, 0.0), 3: (0.995, 0.0), 4: (1.0, 0.0), 5: (0.0014, 0.0)}
 
 
 def say(msg):
@@ -35,8 +39,9 @@ def gpu():
 
 
 def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True, schedule=None, sample=False,
-               global_gap=None):
-    """global_gap: optional function step -> threshold of the row-wide early-commit rule."""
+               global_gap=None, kl=None):
+    """global_gap: optional function step -> threshold of the row-wide early-commit rule.
+    kl: optional (kl_threshold, kl_min_prob) of the KL stability rule, applied at every step."""
     """Lock-step decode: oracle on the host (optionally on a subset of batch rows), library on
     the GPU over the whole batch; compares every step and the final state."""
     from gen.device import DeviceGenerator
@@ -46,7 +51,8 @@ def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True, s
     tokens0, masked0 = run.traj.initial_canvas()
     g = gpu.GpuJot(gpu.params_of(cfg), tokens0, masked0)
     dgen = DeviceGenerator(cfg, run.traj.target, run.traj.rival)
-    logits = dgen.alloc_logits(poison=True)
+    bufs = [dgen.alloc_logits(poison=True), dgen.alloc_logits(poison=True) if kl else None]
+    n_stable = 0
     followed = np.zeros(cfg.B, bool)
     followed[run.batch_rows] = True
     steps = cfg.steps + 16 if max_steps is None else max_steps
@@ -60,21 +66,25 @@ def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True, s
         frac = float(np.float32(frac))
         u = run.draw_uniforms(n) if sample else None
         gg = None if global_gap is None else float(np.float32(global_gap(n)))
-        rec, T, R, rows = run.next_step(nt, frac, u, gg)
+        rec, T, R, rows = run.next_step(nt, frac, u, gg, kl)
+        n_stable += int(rec.stable.sum())
+        logits, prev = (bufs[n % 2], bufs[(n - 1) % 2]) if kl else (bufs[0], None)   # ping-pong under the KL rule
         n_gpu = g.active_count()
         if use_device_gen:
             dgen.set_planted(T, R)
             dgen.fill(logits, n, J.jot_active_list(g.h), n_gpu)
         else:
             gpu.upload_rows(logits, act_full, rows, cfg.dtype)
-        g.step(logits, n_transfer=nt, transfer_frac=frac, uniforms=u, global_gap=gg)
+        g.step(logits, n_transfer=nt, transfer_frac=frac, uniforms=u, global_gap=gg, kl=kl, prev_logits=prev)
         last = g.last()
         sel = followed[last["active"] // cfg.L] if batch_rows is not None else None
         gpu.compare_step(last, rec, act_full, TOL[cfg.dtype], sel)
         n_done = n
         if n % 32 == 0:
             say(f"  step {n}: examined {last['active'].size}, oracle rows {act_full.size}")
-    say(f"  finished after {n_done} steps, bumps={run.n_bumps}")
+    say(f"  finished after {n_done} steps, bumps={run.n_bumps}, stable={n_stable}")
+    if kl:
+        assert n_stable > 0, "the stability rule never fired: the case tests nothing"
     # final state of the followed rows
     st = run.state
     tok, msk, cst = g.tokens(), g.masked(), g.commit_step()
@@ -340,3 +350,26 @@ def test_config4_rowwide_rule_with_schedule_and_sampling(gpu):
 def test_config5_rowwide_rule_short(gpu):
     cfg = CONFIGS[5].replace(B=3, steps=40, conv="mixture")
     run_parity(gpu, cfg, batch_rows=[0, 2], max_steps=40, global_gap=lambda n: 3.0)
+
+
+# --------------------------------------------------------------------------- KL stability rule
+
+def test_config2_with_stability_rule(gpu):
+    cfg = CONFIGS[2].replace(steps=40, L=64 + 128)
+    run_parity(gpu, cfg, kl=(KL_CASES[2]))
+
+
+def test_config4_blockwise_stability_rule_with_schedule_and_sampling(gpu):
+    cfg = CONFIGS[4].replace(B=4, L=128 + 96, steps=96)
+    run_parity(gpu, cfg, batch_rows=[1, 2], sample=True, kl=KL_CASES[4],
+               schedule=lambda n: (np.ones(cfg.B, np.int32), 0.0))
+
+
+def test_config5_stability_rule_short(gpu):
+    cfg = CONFIGS[5].replace(B=3, steps=40, conv="mixture")
+    run_parity(gpu, cfg, batch_rows=[0, 2], max_steps=40, kl=KL_CASES[5])
+
+
+def test_config3_bf16_stability_rule_short(gpu):
+    cfg = CONFIGS[3].replace(B=2, steps=32, dtype=BF16)
+    run_parity(gpu, cfg, max_steps=32, kl=KL_CASES[3])
