@@ -237,7 +237,7 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
         int occ_kl = 0;
         const void* kfn_kl = p->dtype == JOT_F32 ? reinterpret_cast<const void*>(jot_vocab_reduce_kl_kernel<JotF32KL>)
                                                  : reinterpret_cast<const void*>(jot_vocab_reduce_kl_kernel<JotBF16KL>);
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_kl, kfn_kl, reduce_wg, 0) != hipSuccess || occ_kl < 1)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_kl, kfn_kl, p->dtype == JOT_F32 ? JotF32KL::WG : JotBF16KL::WG, 0) != hipSuccess || occ_kl < 1)
             occ_kl = kDefaultWgPerCu;
         if (occ_kl > kMaxWgPerCu) occ_kl = kMaxWgPerCu;
         s->grid_reduce_kl = cus * occ_kl;
