@@ -373,3 +373,8 @@ def test_config5_stability_rule_short(gpu):
 def test_config3_bf16_stability_rule_short(gpu):
     cfg = CONFIGS[3].replace(B=2, steps=32, dtype=BF16)
     run_parity(gpu, cfg, max_steps=32, kl=KL_CASES[3])
+
+
+def test_config5_full_size_stability_rule_first_steps(gpu):
+    # full batch, the launch shape bench.py --kl times; the oracle follows one batch row
+    run_parity(gpu, CONFIGS[5], batch_rows=[17], max_steps=3, kl=KL_CASES[5])
