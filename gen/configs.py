@@ -39,7 +39,7 @@ class JotConfig:
     amp: float = 8.0        # sigmoid amplitude A
     width: float = 2.0      # sigmoid width s (steps)
     rival_frac: float = 0.0 # share of positions with a near-tying second planted token
-    base: str = "partition" # level the planted logit is measured from (see planted_base)
+    base: str = "partition" # 'partition' | 'noise_max' | 'literal': level the planted logit is measured from
 
     def replace(self, **kw) -> "JotConfig":
         return dataclasses.replace(self, **kw)
@@ -56,7 +56,12 @@ class JotConfig:
         """'partition': ln(V) + sigma^2/2, the log partition function of the Gaussian noise, so a
         planted logit base + x has probability about sigmoid(x).  'noise_max': the 1 - 1/V
         quantile of the noise, i.e. the typical largest noise logit of a row (used with the
-        ratio signal, where the target must clear the runner-up by ln(tau))."""
+        ratio signal, where the target must clear the runner-up by ln(tau)).  'literal': 4, so that
+        the single-step trajectory base - 4 + U[0, 8] is the bare offset U[0, 8] on top of the
+        noise (degenerate on purpose: nothing reaches a probability threshold, everything clears
+        a ratio threshold below 1)."""
+        if self.base == "literal":
+            return 4.0
         if self.base == "partition":
             return math.log(self.V) + 0.5 * self.noise_scale ** 2
         from scipy import stats

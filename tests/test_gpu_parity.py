@@ -147,6 +147,12 @@ def test_config1_single_step(gpu, mode, tau_max, tau_min):
     assert run_parity(gpu, cfg, max_steps=1) == 1
 
 
+def test_config1_bare_offset_finalizes_none_or_all(gpu):
+    cfg = CONFIGS[1].replace(base="literal")
+    assert run_parity(gpu, cfg, max_steps=1) == 1
+    assert run_parity(gpu, cfg.replace(conf_mode=CONF_RATIO, tau_max=0.9, tau_min=0.9), max_steps=1) == 1
+
+
 def test_config1_host_uploaded_rows(gpu):
     # same case with rows generated on the host and copied in: independent of the device generator
     assert run_parity(gpu, CONFIGS[1], max_steps=1, use_device_gen=False) == 1

@@ -26,6 +26,16 @@ def test_config1_single_step(mode, tau_max, tau_min):
     assert rec.phi[0] == 0.5 and rec.phi[20] == 0.0
 
 
+def test_config1_with_the_bare_offset_finalizes_none_or_all():
+    # planted logit = U[0, 8] on top of unit noise at V = 32000: p_target ~ e^8 / (e^8 + V e^0.5) ~ 0.05 at most,
+    # a little more where the target's own noise draw is high
+    cfg = CONFIGS[1].replace(base="literal")
+    rec, *_ = LockstepRun(cfg, threads=4).next_step()
+    assert rec.commit.sum() == 0 and rec.p1.max() < 0.25
+    rec, *_ = LockstepRun(cfg.replace(conf_mode=CONF_RATIO, tau_max=0.9, tau_min=0.9), threads=4).next_step()
+    assert rec.commit.all() and np.all(rec.conf >= 1.0)
+
+
 SMALL = {
     2: dict(V=4096, L=64 + 48, steps=40),
     3: dict(V=4096, B=3, L=128 + 40, steps=32),
