@@ -29,7 +29,10 @@ inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 constexpr int kDefaultWgPerCu = 4;
 constexpr int kMaxWgPerCu = 16;
 constexpr int kFallbackCus = 256;
-constexpr int kItemsPerWg = 4;
+#ifndef JOT_ITEMS_PER_WG
+#define JOT_ITEMS_PER_WG 4
+#endif
+constexpr int kItemsPerWg = JOT_ITEMS_PER_WG;
 constexpr int kPerRowStepMax = 2048;   // longest per-row examined list handled by the one-launch row kernel
 
 struct Layout {
