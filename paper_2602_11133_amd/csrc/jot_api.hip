@@ -151,18 +151,32 @@ bool stream_is_capturing(hipStream_t st)
 // Second half of the compaction (and, if `count_rows`, the first half too): ordered writes of the
 // next examined list, the commit log, the mask and its bit image, the counters; its last
 // workgroup closes the step (flips the double buffers in the device-side epoch).
-int enqueue_compaction(jot_state* s, bool creating, hipStream_t st, bool count_rows)
+JotWriteIO write_io(jot_state* s)
+{
+    JotWriteIO w;
+    w.masked = s->at<uint8_t>(s->lay.masked);
+    w.commit_step = s->at<int32_t>(s->lay.commit_step);
+    w.tokens = s->at<int32_t>(s->lay.tokens);
+    w.commit_log = s->at<int32_t>(s->lay.commit_log);
+    w.resolved_bits = s->at<uint64_t>(s->lay.resolved_bits);
+    w.anomalies = s->at<unsigned long long>(s->lay.anomalies);
+    w.host_out = s->host_dev;
+    w.sample_count = s->at<int32_t>(s->lay.sample_count);
+    return w;
+}
+
+// count_rows / write_rows: which of the two compaction passes still have to be launched (a step's
+// per-row kernel may have done the first, or both).
+int enqueue_compaction(jot_state* s, bool creating, hipStream_t st, bool count_rows, bool write_rows = true)
 {
     if (count_rows)
         hipLaunchKernelGGL(jot_row_count_kernel, dim3(s->p.B), dim3(JOT_WG), 0, st, s->compact, s->frame,
                            creating ? 1 : 0, s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
                            s->at<int32_t>(s->lay.row_block), s->at<int32_t>(s->lay.row_n_commit));
-    hipLaunchKernelGGL(jot_row_write_kernel, dim3(s->p.B), dim3(JOT_WG), 0, st, s->compact, s->frame,
-                       creating ? 1 : 0, s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
-                       s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.row_block),
-                       s->at<int32_t>(s->lay.row_n_commit), s->at<int32_t>(s->lay.commit_log),
-                       s->at<uint64_t>(s->lay.resolved_bits), s->at<unsigned long long>(s->lay.anomalies),
-                       s->host_dev, s->at<int32_t>(s->lay.sample_count));
+    if (write_rows)
+        hipLaunchKernelGGL(jot_row_write_kernel, dim3(s->p.B), dim3(JOT_WG), 0, st, s->compact, s->frame,
+                           creating ? 1 : 0, write_io(s), s->at<int32_t>(s->lay.row_block),
+                           s->at<int32_t>(s->lay.row_n_commit));
     if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     // The kernel above also wrote the new counters into pinned host memory.  Outside stream
     // capture the host waits on an event recorded here; a captured step may be replayed any number
@@ -457,10 +471,13 @@ int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t 
     sio.sample_list = dio.sample_list;
     sio.sample_count = dio.sample_count;
 
+    // a single batch row without sampling: the per-row kernel also does the write pass
+    const bool one_launch = s->per_row_step && p.B == 1 && !uniforms_dev;
     if (s->per_row_step) {
         hipLaunchKernelGGL(jot_row_step_kernel, dim3(p.B), dim3(JOT_WG), 0, st, dprm, dio, sprm, sio,
-                           s->compact, s->frame, s->at<uint8_t>(s->lay.masked),
-                           s->at<int32_t>(s->lay.row_block), s->at<int32_t>(s->lay.row_n_commit));
+                           s->compact, s->frame, write_io(s),
+                           s->at<int32_t>(s->lay.row_block), s->at<int32_t>(s->lay.row_n_commit),
+                           one_launch ? 1 : 0);
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     } else {
         hipLaunchKernelGGL(jot_decide_kernel, dim3((unsigned)((n + JOT_WG - 1) / JOT_WG)), dim3(JOT_WG), 0, st,
@@ -486,7 +503,7 @@ int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t 
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     }
     s->step = step;
-    return enqueue_compaction(s, /*creating=*/false, st, /*count_rows=*/!s->per_row_step);
+    return enqueue_compaction(s, /*creating=*/false, st, /*count_rows=*/!s->per_row_step, /*write_rows=*/!one_launch);
 }
 
 int64_t jot_active_count(jot_state* s)

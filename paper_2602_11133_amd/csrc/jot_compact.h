@@ -54,11 +54,17 @@ __device__ __forceinline__ int jot_block_reduce_sum(int v, int* lds)
 
 // Pass 1: per batch row, the block currently being decoded and the two counts.
 // Called by every thread of the workgroup that owns row b (contains barriers); lds: JOT_WAVES ints.
-__device__ __forceinline__ void jot_row_count(const JotCompactParams& prm, int32_t step, int b,
-                                              const uint8_t* __restrict__ masked,
-                                              const int32_t* __restrict__ commit_step,
-                                              int32_t* __restrict__ row_block, int32_t* __restrict__ row_n_active,
-                                              int32_t* __restrict__ row_n_commit, int* lds)
+struct JotRowCounts {
+    int blk;        // block being decoded (0 outside block mode)
+    int n_act;      // positions of the row the next step examines
+    int n_com;      // positions of the row finalized in this step
+};
+
+__device__ __forceinline__ JotRowCounts jot_row_count(const JotCompactParams& prm, int32_t step, int b,
+                                                      const uint8_t* masked, const int32_t* commit_step,
+                                                      int32_t* __restrict__ row_block,
+                                                      int32_t* __restrict__ row_n_active,
+                                                      int32_t* __restrict__ row_n_commit, int* lds)
 {
     const int64_t base = (int64_t)b * prm.L;
     int first = 0x7fffffff;
@@ -87,6 +93,9 @@ __device__ __forceinline__ void jot_row_count(const JotCompactParams& prm, int32
         row_n_active[b] = n_act;
         row_n_commit[b] = n_com;
     }
+    JotRowCounts out;
+    out.blk = blk; out.n_act = n_act; out.n_com = n_com;
+    return out;         // the same in every thread of the workgroup
 }
 
 // `creating`: the pass that builds the first examined list when a state is created; it matches
@@ -99,46 +108,44 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_count_kernel(
     __shared__ int lds[JOT_WAVES];
     const int half = frame.epoch->parity;
     const int32_t step = creating ? -1 : frame.epoch->steps_done + 1;
-    jot_row_count(prm, step, blockIdx.x, masked, commit_step, row_block, frame.row_counts[half ^ 1], row_n_commit, lds);
+    (void)jot_row_count(prm, step, blockIdx.x, masked, commit_step, row_block, frame.row_counts[half ^ 1], row_n_commit, lds);
 }
 
-// Pass 2: exclusive prefix over rows, then ordered writes.
-__global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
-    JotCompactParams prm, JotFrame frame, int creating, uint8_t* __restrict__ masked,
-    const int32_t* __restrict__ commit_step, const int32_t* __restrict__ tokens,
-    const int32_t* __restrict__ row_block, const int32_t* __restrict__ row_n_commit,
-    int32_t* __restrict__ commit_log, uint64_t* __restrict__ resolved_bits,
-    const unsigned long long* __restrict__ anomalies, JotHostBlock* __restrict__ host_out,
-    int32_t* __restrict__ sample_count)
+// Arrays of the write pass, all in the caller's workspace (host_out: mapped pinned host memory).
+struct JotWriteIO {
+    uint8_t* masked;
+    const int32_t* commit_step;
+    const int32_t* tokens;
+    int32_t* commit_log;
+    uint64_t* resolved_bits;
+    const unsigned long long* anomalies;
+    JotHostBlock* host_out;
+    int32_t* sample_count;
+};
+
+// Pass 2 for batch row b, given where its slices start: act_base = examined positions of the rows
+// before it (next step's list), log_base = commit-log entries before its own, blk = its block.
+// Called by every thread of the workgroup (contains barriers); wave_act / wave_com: JOT_WAVES ints.
+// The workgroup that arrives last closes the step.
+__device__ __forceinline__ void jot_row_write(const JotCompactParams& prm, const JotFrame& frame, int creating,
+                                              const JotWriteIO& io, int b, int64_t act_base, int64_t log_base,
+                                              int blk, int* wave_act, int* wave_com)
 {
     const int half = frame.epoch->parity;
     const int32_t step = creating ? -1 : frame.epoch->steps_done + 1;
-    const int32_t* __restrict__ row_n_active = frame.row_counts[half ^ 1];
-    const JotCounters* __restrict__ cnt_in = frame.counters[half];
-    JotCounters* __restrict__ cnt_out = frame.counters[half ^ 1];
+    const JotCounters* cnt_in = frame.counters[half];
+    JotCounters* cnt_out = frame.counters[half ^ 1];
     int32_t* __restrict__ active_out = frame.active[half ^ 1];
-    __shared__ int lds[JOT_WAVES];
-    __shared__ int wave_act[JOT_WAVES], wave_com[JOT_WAVES];
-    const int b = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t base = (int64_t)b * prm.L;
-
-    int pa = 0, pc = 0;
-    for (int k = threadIdx.x; k < b; k += JOT_WG) {
-        pa += row_n_active[k];
-        pc += row_n_commit[k];
-    }
-    const int64_t act_base = jot_block_reduce_sum(pa, lds);
-    const int64_t com_prefix = jot_block_reduce_sum(pc, lds);
-    const int64_t log_base = cnt_in->n_log + com_prefix;
-    const int blk = row_block[b];
+    const int64_t n_examined = cnt_in->n_active;
 
     int run_act = 0, run_com = 0;
     for (int c0 = 0; c0 < prm.L; c0 += JOT_WG) {
         const int i = c0 + threadIdx.x;
         const bool in = i < prm.L;
-        const bool was = in && masked[base + i] != 0;
-        const bool com = was && commit_step[base + i] == step;
+        const bool was = in && io.masked[base + i] != 0;
+        const bool com = was && io.commit_step[base + i] == step;
         const bool still = was && !com;
         const bool elig = still &&
             (prm.block_size <= 0 || jot_floor_div(i - prm.gen_start, prm.block_size) == blk);
@@ -150,7 +157,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
             wave_act[wave] = __popcll(m_act);
             wave_com[wave] = __popcll(m_com);
             if (c0 + wave * 64 < prm.words_per_row * 64)
-                resolved_bits[(int64_t)b * prm.words_per_row + ((c0 + wave * 64) >> 6)] = m_res;
+                io.resolved_bits[(int64_t)b * prm.words_per_row + ((c0 + wave * 64) >> 6)] = m_res;
         }
         __syncthreads();
         int off_act = run_act, off_com = run_com, tot_act = 0, tot_com = 0;
@@ -163,11 +170,11 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
         if (elig)
             active_out[act_base + off_act + __popcll(m_act & below)] = (int32_t)(base + i);
         if (com) {
-            int32_t* e = commit_log + 3 * (log_base + off_com + __popcll(m_com & below));
+            int32_t* e = io.commit_log + 3 * (log_base + off_com + __popcll(m_com & below));
             e[0] = step;
             e[1] = (int32_t)(base + i);
-            e[2] = tokens[base + i];
-            masked[base + i] = 0;
+            e[2] = io.tokens[base + i];
+            io.masked[base + i] = 0;
         }
         run_act += tot_act;
         run_com += tot_com;
@@ -176,7 +183,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
     if (b == prm.B - 1 && threadIdx.x == 0) {
         cnt_out->n_active = act_base + run_act;
         cnt_out->n_log = log_base + run_com;
-        cnt_out->n_examined = cnt_in->n_active;
+        cnt_out->n_examined = n_examined;
         cnt_out->reserved = 0;
     }
     // The workgroup that arrives last closes the step: every other workgroup has finished reading
@@ -189,21 +196,42 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
         if (arrived == (uint32_t)prm.B - 1u) {
             __threadfence();
             // device-scope loads: the numbers were written by the workgroup of the last row
-            host_out->c.n_active = __hip_atomic_load(&cnt_out->n_active, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            host_out->c.n_log = __hip_atomic_load(&cnt_out->n_log, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            host_out->c.n_examined = __hip_atomic_load(&cnt_out->n_examined, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            host_out->c.reserved = 0;
-            host_out->anomalies = *anomalies;
+            io.host_out->c.n_active = __hip_atomic_load(&cnt_out->n_active, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            io.host_out->c.n_log = __hip_atomic_load(&cnt_out->n_log, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            io.host_out->c.n_examined = __hip_atomic_load(&cnt_out->n_examined, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            io.host_out->c.reserved = 0;
+            io.host_out->anomalies = __hip_atomic_load(io.anomalies, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const int32_t done = frame.epoch->steps_done + (creating ? 0 : 1);
-            host_out->steps_done = done;
-            host_out->parity = half ^ 1;
-            *sample_count = 0;            // the sampling work list of this step has been consumed
+            io.host_out->steps_done = done;
+            io.host_out->parity = half ^ 1;
+            *io.sample_count = 0;         // the sampling work list of this step has been consumed
             frame.epoch->rows_done = 0u;
             frame.epoch->steps_done = done;
             frame.epoch->parity = half ^ 1;
             __threadfence_system();
         }
     }
+}
+
+// Pass 2 as a launch of its own: exclusive prefix over the rows' counts, then the ordered writes.
+__global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
+    JotCompactParams prm, JotFrame frame, int creating, JotWriteIO io,
+    const int32_t* __restrict__ row_block, const int32_t* __restrict__ row_n_commit)
+{
+    const int half = frame.epoch->parity;
+    const int32_t* __restrict__ row_n_active = frame.row_counts[half ^ 1];
+    __shared__ int lds[JOT_WAVES];
+    __shared__ int wave_act[JOT_WAVES], wave_com[JOT_WAVES];
+    const int b = blockIdx.x;
+    int pa = 0, pc = 0;
+    for (int k = threadIdx.x; k < b; k += JOT_WG) {
+        pa += row_n_active[k];
+        pc += row_n_commit[k];
+    }
+    const int64_t act_base = jot_block_reduce_sum(pa, lds);
+    const int64_t com_prefix = jot_block_reduce_sum(pc, lds);
+    const int64_t log_base = frame.counters[half]->n_log + com_prefix;
+    jot_row_write(prm, frame, creating, io, b, act_base, log_base, row_block[b], wave_act, wave_com);
 }
 
 // Copy of the caller's initial canvas into the workspace.

@@ -10,13 +10,19 @@
 #include "jot_decide.h"
 #include "jot_schedule.h"
 
+//
+// With a single batch row (the setting of the paper's experiments) nothing is left for a second
+// launch to wait for, and the same workgroup goes on to the write pass of the compaction
+// (`write_too`; the host asks for it only when B == 1 and the step does not sample its tokens,
+// because the sampling kernel runs between the two passes).
 __global__ __launch_bounds__(JOT_WG) void jot_row_step_kernel(
     JotDecideParams dprm, JotDecideIO dio, JotScheduleParams sprm, JotScheduleIO sio,
-    JotCompactParams cprm, JotFrame frame, const uint8_t* __restrict__ masked,
-    int32_t* __restrict__ row_block, int32_t* __restrict__ row_n_commit)
+    JotCompactParams cprm, JotFrame frame, JotWriteIO wio,
+    int32_t* __restrict__ row_block, int32_t* __restrict__ row_n_commit, int write_too)
 {
     __shared__ int lds[JOT_WAVES];
     __shared__ int wave_eq[JOT_WAVES];
+    __shared__ int wave_com[JOT_WAVES];
     __shared__ double dlds[JOT_WAVES];
     const int half = frame.epoch->parity;
     const int32_t step = frame.epoch->steps_done + 1;
@@ -39,5 +45,10 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_step_kernel(
         jot_rowwide_row(sprm, sio, step, base, n, dlds, lds);
         __syncthreads();
     }
-    jot_row_count(cprm, step, b, masked, dio.commit_step, row_block, frame.row_counts[half ^ 1], row_n_commit, lds);
+    const JotRowCounts rc = jot_row_count(cprm, step, b, wio.masked, dio.commit_step, row_block,
+                                          frame.row_counts[half ^ 1], row_n_commit, lds);
+    if (write_too) {        // B == 1: this row's slices start where the lists start
+        __syncthreads();
+        jot_row_write(cprm, frame, /*creating=*/0, wio, b, 0, frame.counters[half]->n_log, rc.blk, wave_eq, wave_com);
+    }
 }
