@@ -177,3 +177,16 @@ double jot_oracle_kl_row(const void *row_now, const void *row_prev, int dtype, i
     }
     return kl;
 }
+
+/* jot_oracle_kl_row over the rows selected by do_row (others get NaN); rows are independent,
+ * so threads take whole rows. */
+void jot_oracle_kl_rows(const void *rows_now, const void *rows_prev, int dtype, int64_t n_rows, int32_t V,
+                        const uint8_t *do_row, double *out, int n_threads)
+{
+    const int64_t esz = dtype == 0 ? 4 : 2;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads > 0 ? n_threads : 1)
+    for (int64_t k = 0; k < n_rows; k++)
+        out[k] = do_row[k] ? jot_oracle_kl_row((const char *)rows_now + k * V * esz,
+                                               (const char *)rows_prev + k * V * esz, dtype, V)
+                           : NAN;
+}

@@ -101,6 +101,9 @@ def _load():
         lib.jot_oracle_sample_row.restype = ctypes.c_int32
         lib.jot_oracle_kl_row.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int32]
         lib.jot_oracle_kl_row.restype = ctypes.c_double
+        lib.jot_oracle_kl_rows.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
+                                           ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        lib.jot_oracle_kl_rows.restype = None
         _lib = lib
     return _lib
 
@@ -153,6 +156,19 @@ def kl_row(row_now: np.ndarray, row_prev: np.ndarray, dtype: int) -> float:
     a = _check_rows(row_now.reshape(1, -1), dtype)
     b = _check_rows(row_prev.reshape(1, -1), dtype)
     return float(_load().jot_oracle_kl_row(a.ctypes.data, b.ctypes.data, dtype, a.shape[1]))
+
+
+def kl_rows(rows_now: np.ndarray, rows_prev: np.ndarray, dtype: int, select: np.ndarray, threads: int = 1) -> np.ndarray:
+    """kl_row for the rows where `select` is true (NaN elsewhere), rows spread over threads."""
+    a = _check_rows(rows_now, dtype)
+    b = _check_rows(rows_prev, dtype)
+    assert a.shape == b.shape
+    sel = np.ascontiguousarray(select, np.uint8)
+    out = np.full(a.shape[0], np.nan)
+    if a.shape[0]:
+        _load().jot_oracle_kl_rows(a.ctypes.data, b.ctypes.data, dtype, a.shape[0], a.shape[1], sel.ctypes.data,
+                                   out.ctypes.data, int(threads))
+    return out
 
 
 @dataclass
@@ -332,8 +348,7 @@ class OracleState:
         if kl_threshold is None:
             return stable, kl
         had_prev = self.last_ok_step.reshape(-1)[act] == self.step_index
-        for k in np.flatnonzero(ok & had_prev):
-            kl[k] = kl_row(rows[k], prev_rows[k], self.params.dtype)
+        kl = kl_rows(rows, prev_rows, self.params.dtype, ok & had_prev, self.threads)
         with np.errstate(invalid="ignore"):
             stable = ok & had_prev & (kl <= kl_threshold) & (p1 >= kl_min_prob)
         return stable, kl

@@ -311,7 +311,8 @@ def test_c_level_mistake_is_caught(name, monkeypatch, tmp_path):
     subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", str(lib), str(cfile), "-lm"])
     good = O._load()
     mut = ctypes.CDLL(str(lib))
-    for fn in ("jot_oracle_row_stats", "jot_oracle_softmax_row", "jot_oracle_sample_row", "jot_oracle_kl_row"):
+    for fn in ("jot_oracle_row_stats", "jot_oracle_softmax_row", "jot_oracle_sample_row", "jot_oracle_kl_row",
+               "jot_oracle_kl_rows"):
         getattr(mut, fn).argtypes = getattr(good, fn).argtypes
         getattr(mut, fn).restype = getattr(good, fn).restype
     monkeypatch.setattr(O, "_lib", mut)
