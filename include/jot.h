@@ -232,6 +232,9 @@ const float*   jot_last_tau(const jot_state* s);
 /* per examined position: bit 0 = passed Eq. 6, bit 1 = picked by the transfer schedule,
  * bit 2 = finalized by the row-wide early-commit rule, bit 3 = stable under the KL rule */
 const uint8_t* jot_last_flags(const jot_state* s);
+/* per examined position: the top-2 LOGIT gap l_(1) - l_(2) that the row-wide rule averages
+ * (+inf if only one logit is finite) */
+const float*   jot_last_gap(const jot_state* s);
 /* per examined position: D(pi_now || pi_prev) of a step run with enable_kl; NaN where the position
  * has no previous distribution or no softmax, and after steps run without the rule */
 const float*   jot_last_kl(const jot_state* s);

@@ -267,6 +267,7 @@ class StepRecord:
     gap_row: np.ndarray = None      # [B] mean top-2 logit gap of the row's examined positions (nan: none)
     cdf_margin: np.ndarray = None   # [A] with sampling: distance of u from the nearer edge of the
                                     #     chosen token's CDF interval (inf where nothing is sampled)
+    gap: np.ndarray = None          # [A] top-2 logit gap l_(1) - l_(2) (+inf: one finite logit; nan: no softmax)
 
 
 @dataclass
@@ -337,8 +338,10 @@ class OracleState:
                 v, lo, hi = sample_row(rows[k], p.dtype, u)
                 final[k] = v
                 margin[k] = min(u - lo, hi - u)
+        with np.errstate(invalid="ignore"):
+            gap = np.where(ok, m1 - m2, np.nan)
         return StepRecord(self.step_index + 1, act, a, p1, p2, conf, tau, phi, commit, st,
-                          exit_, sched, k_row, final, stable, kl, rowwide, gap_row, margin)
+                          exit_, sched, k_row, final, stable, kl, rowwide, gap_row, margin, gap)
 
     def _stable(self, act, rows, prev_rows, p1, ok, kl_threshold, kl_min_prob):
         """KL stability rule; needs the position to have been examined, with a softmax, in the

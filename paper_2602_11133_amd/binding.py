@@ -11,7 +11,7 @@ import numpy as np
 __all__ = [
     "JOT_F32", "JOT_BF16", "JOT_CONF_RATIO", "JOT_CONF_MAXPROB", "JOT_CONF_PROBGAP",
     "JotParams", "JotError", "load_library", "library_path",
-    "jot_workspace_bytes", "jot_init_state", "jot_step", "jot_step_scheduled", "jot_step_sampled", "jot_step_ex", "JotStepOptions", "jot_last_flags", "jot_last_kl", "jot_last_final_token", "jot_active_count", "jot_step_index",
+    "jot_workspace_bytes", "jot_init_state", "jot_step", "jot_step_scheduled", "jot_step_sampled", "jot_step_ex", "JotStepOptions", "jot_last_flags", "jot_last_kl", "jot_last_gap", "jot_last_final_token", "jot_active_count", "jot_step_index",
     "jot_anomaly_count", "jot_tokens", "jot_masked", "jot_commit_step", "jot_active_list",
     "jot_commit_log", "jot_examined_list", "jot_last_token", "jot_last_conf", "jot_last_p1",
     "jot_last_p2", "jot_last_tau", "jot_profile_enable", "jot_profile_read", "jot_release",
@@ -76,7 +76,7 @@ def load_library():
         "jot_step_scheduled": (ctypes.c_int, [vp, vp, i64, i64, vp, ctypes.c_float, vp]),
         "jot_step_sampled": (ctypes.c_int, [vp, vp, i64, i64, vp, ctypes.c_float, vp, vp]),
         "jot_step_ex": (ctypes.c_int, [vp, vp, i64, i64, ctypes.POINTER(JotStepOptions), vp]),
-        "jot_last_flags": (vp, [vp]), "jot_last_kl": (vp, [vp]), "jot_last_final_token": (vp, [vp]),
+        "jot_last_flags": (vp, [vp]), "jot_last_kl": (vp, [vp]), "jot_last_gap": (vp, [vp]), "jot_last_final_token": (vp, [vp]),
         "jot_active_count": (i64, [vp]),
         "jot_step_index": (i32, [vp]),
         "jot_anomaly_count": (i64, [vp]),
@@ -175,6 +175,7 @@ def jot_last_p2(s: int) -> int: return _ptr("jot_last_p2", s)
 def jot_last_tau(s: int) -> int: return _ptr("jot_last_tau", s)
 def jot_last_flags(s: int) -> int: return _ptr("jot_last_flags", s)
 def jot_last_kl(s: int) -> int: return _ptr("jot_last_kl", s)
+def jot_last_gap(s: int) -> int: return _ptr("jot_last_gap", s)
 def jot_last_final_token(s: int) -> int: return _ptr("jot_last_final_token", s)
 
 

@@ -550,6 +550,7 @@ const float* jot_last_p1(const jot_state* s) { return s ? s->at<float>(s->lay.la
 const float* jot_last_p2(const jot_state* s) { return s ? s->at<float>(s->lay.last_p2) : nullptr; }
 const float* jot_last_tau(const jot_state* s) { return s ? s->at<float>(s->lay.last_tau) : nullptr; }
 const uint8_t* jot_last_flags(const jot_state* s) { return s ? s->at<uint8_t>(s->lay.last_flags) : nullptr; }
+const float* jot_last_gap(const jot_state* s) { return s ? s->at<float>(s->lay.last_gap) : nullptr; }
 const float* jot_last_kl(const jot_state* s) { return s ? s->at<float>(s->lay.last_kl) : nullptr; }
 
 int jot_profile_enable(jot_state* s, int on)

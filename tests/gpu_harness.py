@@ -118,6 +118,7 @@ class GpuJot:
         out["flags"] = J.device_to_host(J.jot_last_flags(self.h), n, np.uint8)
         out["final"] = J.device_to_host(J.jot_last_final_token(self.h), n, np.int32)
         out["kl"] = J.device_to_host(J.jot_last_kl(self.h), n, np.float32)
+        out["gap"] = J.device_to_host(J.jot_last_gap(self.h), n, np.float32)
         return out
 
 
@@ -171,6 +172,10 @@ def compare_step(gpu_last: dict, rec, act_full: np.ndarray, tol: float, select=N
     np.testing.assert_array_equal((g["flags"] & 2).astype(bool), want_sched)
     want_rowwide = rec.rowwide if rec.rowwide is not None else np.zeros_like(rec.commit)
     np.testing.assert_array_equal((g["flags"] & 4).astype(bool), want_rowwide)
+    if rec.gap is not None:                # both operands are input values: one binary32 rounding
+        fin = ok & np.isfinite(rec.gap)
+        assert np.all(np.abs(g["gap"][fin].astype(np.float64) - rec.gap[fin]) <= 1e-6 * np.maximum(1.0, rec.gap[fin]))
+        assert np.all(g["gap"][ok & np.isposinf(rec.gap)] == np.inf)
     want_stable = rec.stable if rec.stable is not None else np.zeros_like(rec.commit)
     np.testing.assert_array_equal((g["flags"] & 8).astype(bool), want_stable)
     if rec.kl is not None and np.isfinite(rec.kl).any():
