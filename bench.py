@@ -189,7 +189,8 @@ def main():
     esz = cfg.elem_bytes
     buf_bytes = cfg.B * cfg.L * cfg.V * esz
     free, _total = torch.cuda.mem_get_info()
-    resident = int(max(1, min(K, (free * 0.85) // buf_bytes)))
+    # segments no longer than the library's ring of kernel timings (JOT_PROFILE_RING steps)
+    resident = int(max(1, min(K, 64, (free * 0.85) // buf_bytes)))
     bufs = [dgen.alloc_logits(poison=False) for _ in range(resident)]
     stream = torch.cuda.current_stream().cuda_stream
     torch.manual_seed(cfg.seed)

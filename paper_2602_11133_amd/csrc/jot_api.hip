@@ -29,8 +29,10 @@ inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 constexpr int kDefaultWgPerCu = 4;
 constexpr int kMaxWgPerCu = 16;
 constexpr int kFallbackCus = 256;
+// Work items a step aims for per workgroup of the grid.  Measured over whole decode loops on
+// MI355X: 1 is best (each item costs a lane-state exchange; 2 and 4 lose 1-5 %).
 #ifndef JOT_ITEMS_PER_WG
-#define JOT_ITEMS_PER_WG 4
+#define JOT_ITEMS_PER_WG 1
 #endif
 constexpr int kItemsPerWg = JOT_ITEMS_PER_WG;
 constexpr int kPerRowStepMax = 2048;   // longest per-row examined list handled by the one-launch row kernel
