@@ -177,6 +177,12 @@ int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int
  * become current), there is no previous distribution and the rule does not fire.  Vocabulary
  * entries whose probability underflows binary32 relative to the row maximum (below ~1e-38) count
  * as probability 0 in the divergence.
+ *
+ * Compact logits (logits_compact != 0): for decoders that apply the output projection to the
+ * examined positions only.  logits_dev then holds one row per entry of jot_active_list(), in
+ * that order: row r at logits_dev[r*stride_l + v], r < jot_active_count(); stride_b is ignored.
+ * Same alignment rules.  Cannot be combined with enable_kl (the previous step's rows are in the
+ * previous step's order): JOT_ERR_INVALID_ARG.
  */
 typedef struct {
     const int32_t* n_transfer_dev;   /* transfer schedule, see jot_step_scheduled; may be NULL      */
@@ -188,6 +194,7 @@ typedef struct {
     const void*    prev_logits_dev;  /* the previous step's logits (required if enable_kl)          */
     float          kl_threshold;     /* tau_KL >= 0                                                 */
     float          kl_min_prob;      /* tau_conf in [0, 1]                                          */
+    int32_t        logits_compact;   /* != 0: logits_dev is [jot_active_count(), V], see above      */
 } jot_step_options;
 
 int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,

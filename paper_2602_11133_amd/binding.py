@@ -42,6 +42,7 @@ class JotStepOptions(ctypes.Structure):
         ("global_gap", ctypes.c_float),
         ("enable_kl", ctypes.c_int32), ("prev_logits_dev", ctypes.c_void_p),
         ("kl_threshold", ctypes.c_float), ("kl_min_prob", ctypes.c_float),
+        ("logits_compact", ctypes.c_int32),
     ]
 
 

@@ -39,7 +39,7 @@ constexpr int kPerRowStepMax = 2048;   // longest per-row examined list handled 
 
 struct Layout {
     int64_t tokens, masked, commit_step, resolved_bits, active0, active1, counters, epoch, anomalies,
-        partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, last_m1, last_gap, last_final, lse, lse_step, last_kl, sample_list, sample_count, row_block, row_n_active0, row_n_active1,
+        partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, last_m1, last_gap, last_final, lse, lse_step, last_kl, identity, sample_list, sample_count, row_block, row_n_active0, row_n_active1,
         row_n_commit, commit_log, total;
     int64_t n_partials;
     int32_t words_per_row;
@@ -94,6 +94,7 @@ Layout make_layout(const jot_params* p, int target_items)
     l.lse = take(n * 8);
     l.lse_step = take(n * 4);
     l.last_kl = take(n * 4);
+    l.identity = take(n * 4);
     l.sample_list = take(n * 4);
     l.sample_count = take(4);
     l.row_block = take((int64_t)p->B * 4);
@@ -324,7 +325,7 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
                        n, tokens_dev, masked_dev, s->at<int32_t>(s->lay.tokens),
                        s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
                        s->counters(0), s->at<unsigned long long>(s->lay.anomalies), s->frame.epoch,
-                       s->at<int32_t>(s->lay.lse_step));
+                       s->at<int32_t>(s->lay.lse_step), s->at<int32_t>(s->lay.identity));
     int rc2 = (hipGetLastError() == hipSuccess) ? enqueue_compaction(s, /*creating=*/true, st, true) : JOT_ERR_HIP;
     if (rc2 == JOT_OK && hipStreamSynchronize(st) != hipSuccess) rc2 = JOT_ERR_HIP;
     if (rc2 != JOT_OK) {
@@ -369,7 +370,9 @@ int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t 
     const float* uniforms_dev = opt->uniforms_dev;
     const bool do_rowwide = opt->enable_global_gap != 0;
     const bool do_kl = opt->enable_kl != 0;
+    const bool compact = opt->logits_compact != 0;
     if (!s || !logits_dev) return JOT_ERR_NULL_POINTER;
+    if (compact && do_kl) return JOT_ERR_INVALID_ARG;     // the previous step's rows are in another order
     if (do_kl) {
         if (!opt->prev_logits_dev) return JOT_ERR_NULL_POINTER;
         if (reinterpret_cast<uintptr_t>(opt->prev_logits_dev) % 16) return JOT_ERR_MISALIGNED;
@@ -386,11 +389,21 @@ int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t 
     const jot_params& p = s->p;
     const int64_t esz = p.dtype == JOT_F32 ? 4 : 2;
     if (stride_l < p.V) return JOT_ERR_INVALID_ARG;
-    if (p.B > 1 && stride_b < (int64_t)(p.L - 1) * stride_l + p.V) return JOT_ERR_INVALID_ARG;
-    if (stride_b < 0) return JOT_ERR_INVALID_ARG;
+    if (!compact) {
+        if (p.B > 1 && stride_b < (int64_t)(p.L - 1) * stride_l + p.V) return JOT_ERR_INVALID_ARG;
+        if (stride_b < 0) return JOT_ERR_INVALID_ARG;
+    }
     if (reinterpret_cast<uintptr_t>(logits_dev) % 16 || (stride_l * esz) % 16 ||
-        (p.B > 1 && (stride_b * esz) % 16))
+        (!compact && p.B > 1 && (stride_b * esz) % 16))
         return JOT_ERR_MISALIGNED;
+    // A compact tensor has one row per examined entry.  The reduction is handed the identity list
+    // and a canvas length no position reaches, so that "position" r resolves to row r of batch 0.
+    JotFrame reduce_frame = s->frame;
+    int reduce_L = p.L;
+    if (compact) {
+        reduce_frame.active[0] = reduce_frame.active[1] = s->at<int32_t>(s->lay.identity);
+        reduce_L = 0x7fffffff;
+    }
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int32_t step = s->step + 1;           // host-side call count; the kernels use the device epoch
@@ -412,11 +425,11 @@ int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t 
                            s->at<JotPartial>(s->lay.partials), s->target_items_kl, INFINITY);
     else if (p.dtype == JOT_F32)
         hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotF32>, dim3(s->grid_reduce), dim3(JotF32::WG), 0, st,
-                           logits_dev, stride_b, stride_l, p.L, p.V, s->frame,
+                           logits_dev, stride_b, stride_l, reduce_L, p.V, reduce_frame,
                            s->at<JotPartial>(s->lay.partials), s->target_items, INFINITY);
     else
         hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotBF16>, dim3(s->grid_reduce), dim3(JotBF16::WG), 0, st,
-                           logits_dev, stride_b, stride_l, p.L, p.V, s->frame,
+                           logits_dev, stride_b, stride_l, reduce_L, p.V, reduce_frame,
                            s->at<JotPartial>(s->lay.partials), s->target_items, INFINITY);
     if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     if (s->profile && !capturing) {
@@ -496,12 +509,12 @@ int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t 
             hipLaunchKernelGGL(jot_sample_kernel<JotF32>, dim3(grid), dim3(JOT_WG), 0, st, logits_dev, stride_b,
                                stride_l, p.L, p.V, s->frame, s->at<int32_t>(s->lay.sample_list),
                                s->at<int32_t>(s->lay.sample_count), s->at<float>(s->lay.last_m1), uniforms_dev,
-                               s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.last_final));
+                               s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.last_final), compact ? 1 : 0);
         else
             hipLaunchKernelGGL(jot_sample_kernel<JotBF16>, dim3(grid), dim3(JOT_WG), 0, st, logits_dev, stride_b,
                                stride_l, p.L, p.V, s->frame, s->at<int32_t>(s->lay.sample_list),
                                s->at<int32_t>(s->lay.sample_count), s->at<float>(s->lay.last_m1), uniforms_dev,
-                               s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.last_final));
+                               s->at<int32_t>(s->lay.tokens), s->at<int32_t>(s->lay.last_final), compact ? 1 : 0);
         if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     }
     s->step = step;

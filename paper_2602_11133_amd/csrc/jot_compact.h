@@ -239,10 +239,11 @@ __global__ __launch_bounds__(JOT_WG) void jot_init_copy_kernel(
     int64_t n, const int32_t* __restrict__ tokens_in, const uint8_t* __restrict__ masked_in,
     int32_t* __restrict__ tokens, uint8_t* __restrict__ masked, int32_t* __restrict__ commit_step,
     JotCounters* __restrict__ cnt0, unsigned long long* __restrict__ anomalies, JotEpoch* __restrict__ epoch,
-    int32_t* __restrict__ lse_step)
+    int32_t* __restrict__ lse_step, int32_t* __restrict__ identity)
 {
     const int64_t k = (int64_t)blockIdx.x * JOT_WG + threadIdx.x;
     if (k < n) {
+        identity[k] = (int32_t)k;      // "row r is entry r": the examined list of a compact logits tensor
         tokens[k] = tokens_in[k];
         masked[k] = masked_in[k] ? 1 : 0;
         commit_step[k] = 0;

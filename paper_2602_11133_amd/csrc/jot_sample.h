@@ -46,7 +46,8 @@ __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
     const void* __restrict__ logits, int64_t stride_b, int64_t stride_l, int L, int V,
     JotFrame frame, const int32_t* __restrict__ sample_list,
     const int32_t* __restrict__ sample_count, const float* __restrict__ last_m1,
-    const float* __restrict__ uniforms, int32_t* __restrict__ tokens, int32_t* __restrict__ last_final)
+    const float* __restrict__ uniforms, int32_t* __restrict__ tokens, int32_t* __restrict__ last_final,
+    int compact)        // != 0: logits holds one row per examined entry, row r at r * stride_l
 {
     constexpr int VEC = T::VEC;
     constexpr int U = JotSampleShape<T>::U;
@@ -62,8 +63,8 @@ __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
         const int r = sample_list[item];
         const int pos = active[r];
         const int b = pos / L, i = pos - b * L;
-        const char* row = reinterpret_cast<const char*>(logits) +
-                          ((int64_t)b * stride_b + (int64_t)i * stride_l) * T::ESZ;
+        const int64_t row_off = compact ? (int64_t)r * stride_l : (int64_t)b * stride_b + (int64_t)i * stride_l;
+        const char* row = reinterpret_cast<const char*>(logits) + row_off * T::ESZ;
         const jot_u32x4* __restrict__ p = reinterpret_cast<const jot_u32x4*>(row);
         const float shift = -last_m1[r] * JOT_LOG2E;             // exp(l - m1) = 2^(l*log2e + shift)
         const int nvec = V / VEC;

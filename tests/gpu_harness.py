@@ -44,12 +44,16 @@ class GpuJot:
             pass
 
     def step(self, logits: torch.Tensor, stride_b=None, stride_l=None, n_transfer=None, transfer_frac=0.0,
-             uniforms=None, global_gap=None, kl=None, prev_logits=None):
+             uniforms=None, global_gap=None, kl=None, prev_logits=None, compact=False):
         """kl = (kl_threshold, kl_min_prob) turns the KL stability rule on; prev_logits is then the
-        tensor the previous step was given (same layout)."""
-        sb = logits.stride(0) if stride_b is None else stride_b
-        sl = logits.stride(1) if stride_l is None else stride_l
-        if global_gap is not None or kl is not None:     # the general entry point
+        tensor the previous step was given (same layout).  compact: `logits` is [n_examined, stride]
+        with one row per entry of the examined list."""
+        if compact:
+            sb, sl = 0, (logits.stride(0) if stride_l is None else stride_l)
+        else:
+            sb = logits.stride(0) if stride_b is None else stride_b
+            sl = logits.stride(1) if stride_l is None else stride_l
+        if global_gap is not None or kl is not None or compact:     # the general entry point
             opt = J.JotStepOptions()
             if n_transfer is not None:
                 self._nt = torch.from_numpy(np.ascontiguousarray(n_transfer, np.int32)).to(self.dev)
@@ -61,6 +65,7 @@ class GpuJot:
             if global_gap is not None:
                 opt.enable_global_gap = 1
                 opt.global_gap = global_gap
+            opt.logits_compact = 1 if compact else 0
             if kl is not None:
                 assert prev_logits.stride() == logits.stride() and prev_logits.dtype == logits.dtype
                 opt.enable_kl = 1
@@ -120,6 +125,21 @@ class GpuJot:
         out["kl"] = J.device_to_host(J.jot_last_kl(self.h), n, np.float32)
         out["gap"] = J.device_to_host(J.jot_last_gap(self.h), n, np.float32)
         return out
+
+
+def gather_compact(logits: torch.Tensor, active_dev_ptr: int, n: int, pad_elems: int = 0) -> torch.Tensor:
+    """[n, V + pad] tensor holding the rows of the examined positions in list order -- what a decoder
+    that applies its output projection to the examined positions only would produce (test plumbing:
+    the full tensor is gathered by the list the library exposes).  Padding is NaN."""
+    B, L, V = logits.shape
+    if n:
+        idx = torch.from_numpy(J.device_to_host(active_dev_ptr, n, np.int32).astype(np.int64)).to(logits.device)
+    else:
+        idx = torch.zeros(0, dtype=torch.int64, device=logits.device)
+    out = torch.full((max(n, 1), V + pad_elems), float("nan"), dtype=logits.dtype, device=logits.device)
+    if n:
+        out[:n, :V] = logits.view(B * L, V).index_select(0, idx)
+    return out
 
 
 def upload_rows(logits: torch.Tensor, positions: np.ndarray, rows: np.ndarray, dtype: int) -> None:

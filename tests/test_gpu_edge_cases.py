@@ -64,8 +64,9 @@ def to_device(logits: np.ndarray, dtype: int, stride_l: int):
 
 
 def check_case(gpu, p: O.OracleParams, tokens, masked, logit_seq, stride_pad=0, tol=None, clear=True,
-               schedule=None, uniforms=None, global_gap=None, kl=None):
-    """kl: optional list, per step, of (kl_threshold, kl_min_prob) or None: the KL stability rule
+               schedule=None, uniforms=None, global_gap=None, kl=None, compact=False):
+    """compact: give the library a [n_examined, stride] tensor with the examined rows in list order.
+    kl: optional list, per step, of (kl_threshold, kl_min_prob) or None: the KL stability rule
     against the logits of the step before.  schedule: optional list of (n_transfer, frac) per step.  uniforms: optional list of [B, L]
     float32 arrays per step (sampling-based finalization); numbers that fall within GUARD_U of
     an edge of the chosen token's CDF interval are redrawn here (they are inputs)."""
@@ -122,8 +123,13 @@ def check_case(gpu, p: O.OracleParams, tokens, masked, logit_seq, stride_pad=0, 
         if gg is not None:
             assert np.all(~(np.abs(rec.gap_row - gg) < GUARD * max(1.0, abs(gg)))), "row mean sits on the threshold"
         dev = to_device(logits, p.dtype, stride_l)
-        g.step(dev, stride_b=p.L * stride_l, stride_l=stride_l, n_transfer=nt, transfer_frac=frac, uniforms=u,
-               global_gap=gg, kl=klo, prev_logits=dev if prev_dev is None else prev_dev)
+        if compact:
+            small = gpu.gather_compact(dev[:, :, :p.V].contiguous(), J.jot_active_list(g.h), g.active_count(),
+                                       pad_elems=stride_l - p.V)
+            g.step(small, n_transfer=nt, transfer_frac=frac, uniforms=u, global_gap=gg, compact=True)
+        else:
+            g.step(dev, stride_b=p.L * stride_l, stride_l=stride_l, n_transfer=nt, transfer_frac=frac, uniforms=u,
+                   global_gap=gg, kl=klo, prev_logits=dev if prev_dev is None else prev_dev)
         prev_logits, prev_dev = logits, dev
         gpu.compare_step(g.last(), rec, act, tol)
         np.testing.assert_array_equal(g.tokens(), st.tokens)
@@ -624,4 +630,41 @@ def test_stability_rule_argument_errors(gpu):
     assert call(kl_min_prob=1.5) == -1
     assert J.jot_step_index(g.h) == 0
     assert call() == 0 and J.jot_step_index(g.h) == 1
+    g.close()
+
+
+# --------------------------------------------------------------------------- compact logits
+
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+@pytest.mark.parametrize("V,L,block", [(9, 30, 0), (1003, 70, 0), (8200, 50, 5), (40_003, 20, 0), (300_007, 6, 0)])
+def test_compact_logits(gpu, dtype, V, L, block):
+    # one row per examined entry, padded row stride, schedule on; long vocabularies are cut into pieces
+    p, tokens, masked, seq = random_case(300 + V, B=3, L=L, V=V, gs=L // 4, dtype=dtype, conf_mode=O.CONF_MAXPROB,
+                                         tau_max=0.9, tau_min=0.2, gamma=0.6, D=6, steps=3, block_size=block)
+    check_case(gpu, p, tokens, masked, seq, stride_pad=1, compact=True,
+               schedule=[(np.array([1, 0, 2], np.int32), 0.0), (None, 0.25), (None, 0.0)])
+
+
+def test_compact_logits_sampled_and_errors(gpu):
+    import ctypes
+    import paper_2602_11133_amd as J
+    rng = np.random.default_rng(5)
+    B, L, V = 2, 17, 520
+    p = O.OracleParams(B=B, L=L, V=V, dtype=O.F32, conf_mode=O.CONF_MAXPROB, tau_max=0.0, tau_min=0.0, D=0)
+    lg = (rng.standard_normal((B, L, V)) * 1.5).astype(np.float32)
+    masked = rng.random((B, L)) < 0.7
+    u = rng.random((B, L)).astype(np.float32)
+    check_case(gpu, p, np.zeros((B, L), np.int32), masked, [lg], uniforms=[u], compact=True, clear=False)
+    # compact logits cannot be combined with the KL rule
+    jp = J.JotParams(B=B, L=L, V=V, dtype=0, conf_mode=1, tau_max=0.5, tau_min=0.5, gamma=0.5, D=0, eps=0.0,
+                     gen_start=0, block_size=0)
+    g = gpu.GpuJot(jp, np.zeros((B, L), np.int32), masked)
+    dev = to_device(lg, O.F32, V)
+    opt = J.JotStepOptions()
+    opt.logits_compact = 1
+    opt.enable_kl = 1
+    opt.prev_logits_dev = dev.data_ptr()
+    opt.kl_threshold = 0.1
+    assert J.load_library().jot_step_ex(g.h, dev.data_ptr(), 0, V, ctypes.byref(opt), g.stream) == -1
+    assert J.jot_step_index(g.h) == 0
     g.close()

@@ -39,11 +39,12 @@ def gpu():
 
 
 def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True, schedule=None, sample=False,
-               global_gap=None, kl=None):
+               global_gap=None, kl=None, compact=False):
     """Lock-step decode: oracle on the host (optionally on a subset of batch rows), library on
     the GPU over the whole batch; compares every step and the final state.
     global_gap: optional function step -> threshold of the row-wide early-commit rule.
-    kl: optional (kl_threshold, kl_min_prob) of the KL stability rule, applied at every step."""
+    kl: optional (kl_threshold, kl_min_prob) of the KL stability rule, applied at every step.
+    compact: hand the library a [n_examined, V] tensor (rows in list order) instead of [B, L, V]."""
     from gen.device import DeviceGenerator
     say(f"[parity] {cfg.name} B={cfg.B} L={cfg.L} V={cfg.V} dtype={cfg.dtype} mode={cfg.conf_mode} "
         f"tau=({cfg.tau_max},{cfg.tau_min}) block={cfg.block_size} rows={batch_rows}")
@@ -75,7 +76,11 @@ def run_parity(gpu, cfg, batch_rows=None, max_steps=None, use_device_gen=True, s
             dgen.fill(logits, n, J.jot_active_list(g.h), n_gpu)
         else:
             gpu.upload_rows(logits, act_full, rows, cfg.dtype)
-        g.step(logits, n_transfer=nt, transfer_frac=frac, uniforms=u, global_gap=gg, kl=kl, prev_logits=prev)
+        if compact:
+            small = gpu.gather_compact(logits, J.jot_active_list(g.h), n_gpu)
+            g.step(small, n_transfer=nt, transfer_frac=frac, uniforms=u, global_gap=gg, compact=True)
+        else:
+            g.step(logits, n_transfer=nt, transfer_frac=frac, uniforms=u, global_gap=gg, kl=kl, prev_logits=prev)
         last = g.last()
         sel = followed[last["active"] // cfg.L] if batch_rows is not None else None
         gpu.compare_step(last, rec, act_full, TOL[cfg.dtype], sel)
@@ -385,3 +390,20 @@ def test_config5_full_size_stability_rule_first_steps(gpu):
     # full batch, the launch shape bench.py --kl times; the oracle follows one batch row
     # (a threshold just above the bulk of the divergences: fewer inputs to move off the guard band)
     run_parity(gpu, CONFIGS[5], batch_rows=[17], max_steps=2, kl=(0.002, 0.0))
+
+
+# --------------------------------------------------------------------------- compact logits
+
+def test_config2_compact_logits_with_schedule_and_sampling(gpu):
+    cfg = CONFIGS[2].replace(steps=40, L=64 + 160)
+    run_parity(gpu, cfg, compact=True, sample=True, schedule=lambda n: (None, 1.0 / max(1, cfg.steps - n + 1)))
+
+
+def test_config4_compact_logits_blockwise_with_rowwide_rule(gpu):
+    cfg = CONFIGS[4].replace(B=6, L=128 + 96, steps=96)
+    run_parity(gpu, cfg, batch_rows=[0, 2, 5], compact=True, global_gap=lambda n: 6.5)
+
+
+def test_config5_compact_logits_short(gpu):
+    cfg = CONFIGS[5].replace(B=3, steps=24)
+    run_parity(gpu, cfg, batch_rows=[1], max_steps=24, compact=True)
