@@ -66,6 +66,8 @@ def load_probe():
     vp, i64 = ctypes.c_void_p, ctypes.c_int64
     lib.jot_probe_copy.argtypes, lib.jot_probe_copy.restype = [vp, vp, i64, vp], ctypes.c_int
     lib.jot_probe_read.argtypes, lib.jot_probe_read.restype = [vp, i64, vp, vp], ctypes.c_int
+    lib.jot_probe_read_rows.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, i64, i64, i64, ctypes.c_int32, vp, vp]
+    lib.jot_probe_read_rows.restype = ctypes.c_int
     return lib
 
 
@@ -97,6 +99,29 @@ def read_ceiling(torch, buf, reps=3) -> float:
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         assert lib.jot_probe_read(buf.data_ptr(), nbytes, out.data_ptr(), st) == 0
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    return best
+
+
+def read_ceiling_rows(torch, buf, cfg, reps=3) -> float:
+    """Best-of-reps GB/s of a read-only kernel that streams the generated positions' rows of one
+    logits buffer row by row, in the launch shape of the fp32 reduction (one workgroup per CU)."""
+    lib = load_probe()
+    row = cfg.V * cfg.elem_bytes
+    if row % 16:
+        return float("nan")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    nbytes = cfg.B * cfg.n_gen * row
+    best = 0.0
+    for _ in range(reps + 1):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        assert lib.jot_probe_read_rows(buf.data_ptr() + cfg.gen_start * row, cfg.B, cfg.n_gen, cfg.L * row, row, row,
+                                       cus, out.data_ptr(), st) == 0
         e1.record()
         torch.cuda.synchronize()
         best = max(best, nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
@@ -309,6 +334,7 @@ def main():
     }
     if not args.no_ceiling:
         out["plain_read_kernel_GBps"] = read_ceiling(torch, bufs[0])
+        out["same_shape_read_kernel_GBps"] = read_ceiling_rows(torch, bufs[0], cfg)
     del bufs
     torch.cuda.empty_cache()
     if not args.no_cpu:

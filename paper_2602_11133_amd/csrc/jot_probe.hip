@@ -1,6 +1,7 @@
 // Measurement aids, not part of the finalization pass: a plain copy kernel of known size (to
-// calibrate the FETCH_SIZE / WRITE_SIZE hardware counters) and a plain read-and-sum kernel (the
-// read-only streaming ceiling of the device, for comparison with the vocabulary reduction).
+// calibrate the FETCH_SIZE / WRITE_SIZE hardware counters) and two read-and-sum kernels (what a
+// kernel that only loads reaches on the device, for comparison with the vocabulary reduction):
+// a grid-stride one, and one with the reduction's own launch shape and row-by-row pattern.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -30,6 +31,41 @@ __global__ __launch_bounds__(256) void jot_probe_read_kernel(const probe_u32x4* 
     if (acc == 0x9e3779b9u) out[0] = acc;     // practically never true: keeps the loads alive
 }
 
+// Read-only kernel with the launch shape and access pattern of the fp32 vocabulary reduction: one
+// 1024-thread workgroup per CU, workgroup w streams rows w, w + G, ..., eight 16-byte nontemporal
+// loads in flight per thread, whole batches first and one predicated ragged batch.  Rows are laid
+// out as in a [groups, rows_per_group (+ skipped rows), row] tensor.
+__global__ __launch_bounds__(1024) void jot_probe_read_rows_kernel(
+    const char* __restrict__ base, int64_t n_rows, int rows_per_group, int64_t group_stride, int64_t row_stride,
+    int nvec, uint32_t* __restrict__ out)
+{
+    constexpr int WG = 1024, U = 8;
+    uint32_t acc = 0;
+    for (int64_t j = blockIdx.x; j < n_rows; j += gridDim.x) {
+        const int64_t g = j / rows_per_group, i = j - g * rows_per_group;
+        const probe_u32x4* p = reinterpret_cast<const probe_u32x4*>(base + g * group_stride + i * row_stride);
+        int b = 0;
+        for (; b + U * WG <= nvec; b += U * WG) {
+            probe_u32x4 w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) w[u] = __builtin_nontemporal_load(p + b + threadIdx.x + u * WG);
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc += w[u].x ^ w[u].y ^ w[u].z ^ w[u].w;
+        }
+        if (b < nvec) {
+            probe_u32x4 w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = b + threadIdx.x + u * WG;
+                w[u] = __builtin_nontemporal_load(p + (c < nvec ? c : 0));
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc += w[u].x ^ w[u].y ^ w[u].z ^ w[u].w;
+        }
+    }
+    if (acc == 0x9e3779b9u) out[0] = acc;
+}
+
 extern "C" {
 
 // Copies `bytes` (multiple of 16) from src_dev to dst_dev.  Returns the hipError_t of the launch.
@@ -47,6 +83,21 @@ int jot_probe_read(const void* src_dev, int64_t bytes, void* out_dev, void* stre
     if (bytes <= 0 || bytes % 32768) return (int)hipErrorInvalidValue;
     hipLaunchKernelGGL(jot_probe_read_kernel, dim3(256 * 8), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const probe_u32x4*>(src_dev), bytes / 16, static_cast<uint32_t*>(out_dev));
+    return (int)hipGetLastError();
+}
+
+// Streams n_groups * rows_per_group rows of row_bytes (multiple of 16) each: row i of group g starts
+// at src_dev + g * group_stride_bytes + i * row_stride_bytes (all multiples of 16, every row inside
+// the caller's buffer).  `grid` workgroups of 1024 threads.
+int jot_probe_read_rows(const void* src_dev, int32_t n_groups, int32_t rows_per_group, int64_t group_stride_bytes,
+                        int64_t row_stride_bytes, int64_t row_bytes, int32_t grid, void* out_dev, void* stream)
+{
+    if (n_groups <= 0 || rows_per_group <= 0 || grid <= 0 || row_bytes <= 0 || row_bytes % 16 ||
+        row_stride_bytes % 16 || group_stride_bytes % 16 || row_bytes / 16 > 0x7fffffff)
+        return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(jot_probe_read_rows_kernel, dim3(grid), dim3(1024), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const char*>(src_dev), (int64_t)n_groups * rows_per_group, rows_per_group,
+                       group_stride_bytes, row_stride_bytes, (int)(row_bytes / 16), static_cast<uint32_t*>(out_dev));
     return (int)hipGetLastError();
 }
 
