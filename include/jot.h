@@ -257,7 +257,8 @@ const float*   jot_last_kl(const jot_state* s);
 int jot_profile_enable(jot_state* s, int on);
 int jot_profile_read(jot_state* s, int32_t step, float* vocab_reduce_ms);
 
-/* Free the host object and its pinned host counters (device memory is the caller's). */
+/* Free the host object and its pinned host counters (device memory is the caller's).  Waits for
+ * the steps enqueued on this state to finish first; NULL is a no-op. */
 void jot_release(jot_state* s);
 
 const char* jot_strerror(int code);

@@ -602,6 +602,7 @@ int jot_profile_read(jot_state* s, int32_t step, float* vocab_reduce_ms)
 void jot_release(jot_state* s)
 {
     if (!s) return;
+    (void)wait_done(s);       // the last step's final kernel writes into the pinned block freed below
     if (s->profile) (void)jot_profile_enable(s, 0);
     (void)hipEventDestroy(s->done);
     if (s->host) (void)hipHostFree(s->host);
