@@ -50,6 +50,7 @@ def pin_battery():
         ("sched_fraction", S.test_fraction_one_reveals_everything_and_fraction_is_floored),
         ("sched_ties", S.test_equal_confidence_is_ranked_by_position_and_rows_without_softmax_are_skipped),
         ("sched_blocks", S.test_schedule_stays_inside_the_current_block_and_guarantees_termination),
+        ("share_bound", P.test_committed_positions_leave_the_runner_up_a_small_head_to_head_share),
         ("rowwide_mean", R.test_mean_gap_and_all_or_nothing_per_row),
         ("rowwide_inclusive", R.test_threshold_is_inclusive_and_off_by_default),
         ("rowwide_or", R.test_rows_without_softmax_neither_count_nor_commit_and_rule_is_ored),

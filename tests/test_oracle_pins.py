@@ -132,6 +132,36 @@ def test_flip_budget_arithmetic_printed(printed):
     assert round(2 * fb["L"] / (1 + fb["tau"]), fb["digits"]) == fb["printed"]
 
 
+def test_committed_positions_leave_the_runner_up_a_small_head_to_head_share():
+    # Section 5 (proof sketch of the flip bound): at commit time the runner-up holds at most a
+    # 1/(1 + tau) share of the head-to-head probability against the leader -- with the
+    # position's own threshold tau^i under spatial modulation.  Checked on every position a
+    # multi-step decode commits, from the full probability vectors.
+    rng = np.random.default_rng(11)
+    B, L, V, gs = 2, 40, 30, 6
+    p = O.OracleParams(B=B, L=L, V=V, conf_mode=O.CONF_RATIO, tau_max=20.0, tau_min=1.5, gamma=0.5, D=4, gen_start=gs)
+    masked = np.zeros((B, L), bool)
+    masked[:, gs:] = True
+    st = O.OracleState.init(p, np.zeros((B, L), np.int32), masked)
+    n_committed = 0
+    for step in range(12):
+        act = st.active_list()
+        if act.size == 0:
+            break
+        rows = (rng.standard_normal((act.size, V)) * (1.0 + 0.5 * step)).astype(np.float32)
+        rec = st.step(rows)
+        for k in np.flatnonzero(rec.commit):
+            pi = np.sort(O.softmax_row(rows[k], O.F32))[::-1]
+            share = pi[1] / (pi[0] + pi[1])
+            assert share <= 1.0 / (1.0 + rec.tau[k]) + 1e-12
+            assert 2.0 * share <= 2.0 / (1.0 + p.tau_min) + 1e-12       # hence the per-position flip bound
+            n_committed += 1
+        for k in np.flatnonzero(~rec.commit & (rec.status == 0)):       # and the converse up to eps
+            pi = np.sort(O.softmax_row(rows[k], O.F32))[::-1]
+            assert pi[1] / (pi[0] + pi[1]) > 1.0 / (1.0 + rec.tau[k]) - 1e-9
+    assert n_committed > 20
+
+
 @pytest.mark.parametrize("seed", range(20))
 def test_top2_and_argmax_brute_force_small_vocab(seed):
     rng = np.random.default_rng(seed)
