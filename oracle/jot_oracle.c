@@ -25,16 +25,14 @@
  * Rows that contain NaN or +inf, or whose entries are all -inf, have no
  * softmax; they are reported with status 1 and S = NaN (the caller must not
  * finalize them).  -inf entries are ordinary: they contribute exp(-inf) = 0.
- * By convention of this library a row whose largest logit lies outside
- * [-4e6, 4e6] is reported the same way: such magnitudes do not occur in model
- * logits, and the convention keeps the supported input domain explicit.
+ * Every other row has a softmax, whatever the size of its entries: the
+ * definition only involves differences from the row maximum.
  */
 #include <math.h>
 #include <stdint.h>
 #include <string.h>
 
 enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
-#define ORACLE_LOGIT_LIMIT 4.0e6   /* supported range of a row's largest logit */
 
 static double widen(const void *row, int dtype, int64_t v)
 {
@@ -74,7 +72,7 @@ static int row_stats(const void *row, int dtype, int32_t V,
     *a = arg;
     *m1 = best;
     *m2 = second;
-    if (bad || best == -INFINITY || best < -ORACLE_LOGIT_LIMIT || best > ORACLE_LOGIT_LIMIT) {
+    if (bad || best == -INFINITY) {
         *S = NAN;
         return 1;
     }

@@ -23,8 +23,7 @@ the argmax takes the smallest index among equal logits; p2 is the second entry
 of the sorted multiset (a duplicated maximum gives p2 = p1); positions outside
 the canvas contribute nothing to Eq. 3; d = 0 is excluded (i itself is masked);
 D = 0 means no spatial modulation (phi = 0); a row with NaN / +inf logits, or
-only -inf logits, or whose largest logit is outside [-4e6, 4e6] (the library's
-stated input domain), is never finalized.
+only -inf logits, has no softmax and is never finalized.
 
 Transfer schedule (Section 3.2 "Iterative Sampling"; Section 4.2 "Interaction with transfer
 schedules" and "Implementation details"): each step the decoder's own schedule reveals a number

@@ -486,14 +486,26 @@ def test_simultaneous_update_within_a_step():
     assert st.commit_log == [(1, 4, 2), (2, 5, 1)]
 
 
-def test_supported_range_of_the_row_maximum():
-    # library convention: the largest logit must lie in [-4e6, 4e6]; fill values below are fine
-    rows = np.zeros((5, 6), np.float32)
+def test_softmax_is_defined_for_rows_of_any_magnitude():
+    # Section 4.1 defines pi = softmax(l) for every finite row: only differences from the row maximum
+    # enter.  Rows far from zero (where binary32 still resolves the differences) must give the
+    # softmax of the shifted row, fill values of any size count as probability 0.
+    from scipy.special import softmax
+    small = np.array([0.0, 1.0, 2.0, 0.5, -3.0, 2.0], np.float32)
+    want = softmax(small.astype(np.float64))
+    for shift in (2.0 ** 22, -(2.0 ** 22), 1.0e9, -1.0e9, 2.0 ** 100, -(2.0 ** 100)):
+        row = (small.astype(np.float64) * (1.0 if abs(shift) < 2 ** 23 else 0.0) + shift).astype(np.float32)
+        exact = row.astype(np.float64) - float(row.max())         # what binary32 kept of the differences
+        got = O.softmax_row(row, O.F32)
+        np.testing.assert_allclose(got, softmax(exact), rtol=1e-14, atol=0)
+        if abs(shift) < 2 ** 23:
+            np.testing.assert_allclose(got, want, rtol=1e-14, atol=0)
+    rows = np.zeros((4, 6), np.float32)
     rows[0, :] = [-1e30, 1.0, -3e38, 0.0, -1e9, -np.inf]
-    rows[1, :] = 4.0e6
-    rows[2, :] = 4.1e6
-    rows[3, :] = -4.1e6
-    rows[4, :] = [3.9e6, -3.9e6, 0, 0, 0, 0]
+    rows[1, :] = 4.1e6
+    rows[2, :] = -3.0e38
+    rows[3, :] = [3.0e38, -3.0e38, 0, 0, 0, 0]
     a, m1, m2, S, st = O.row_stats(rows, O.F32)
-    assert st.tolist() == [0, 0, 1, 1, 0]
-    assert a[0] == 1 and abs(S[0] - (1 + math.exp(-1))) < 1e-15 and S[1] == 6.0 and S[4] == 1.0
+    assert st.tolist() == [0, 0, 0, 0]
+    assert a.tolist() == [1, 0, 0, 0]
+    assert abs(S[0] - (1 + math.exp(-1))) < 1e-15 and S[1] == 6.0 and S[2] == 6.0 and S[3] == 1.0
