@@ -51,20 +51,22 @@ def too_close(rec: O.StepRecord, L: int = 0, kl=None) -> np.ndarray:
 
 
 class LockstepRun:
-    def __init__(self, cfg: JotConfig, threads: int = 1, batch_rows=None):
+    def __init__(self, cfg: JotConfig, threads: int = 1, batch_rows=None, share=None):
         """batch_rows: optional list of batch rows b to follow (rows are independent decodes);
         the oracle then runs on that sub-batch only, positions are reported in the full
-        canvas numbering."""
+        canvas numbering.  share: another LockstepRun of the same configuration whose trajectory
+        (and hence input adjustments) and row generators this one uses too -- for following a
+        large batch as several sub-batches, one after the other, within each step."""
         self.cfg = cfg
-        self.traj = Trajectory(cfg)
-        self.gen = HostGenerator(cfg, self.traj.target, self.traj.rival, threads)
+        self.traj = share.traj if share else Trajectory(cfg)
+        self.gen = share.gen if share else HostGenerator(cfg, self.traj.target, self.traj.rival, threads)
         tokens, masked = self.traj.initial_canvas()
         self.batch_rows = list(range(cfg.B)) if batch_rows is None else list(batch_rows)
         sub = cfg.replace(B=len(self.batch_rows))
         self.state = O.OracleState.init(oracle_params(sub), tokens[self.batch_rows],
                                         masked[self.batch_rows], threads=threads)
         self.n_bumps = 0
-        self.gen_prev = HostGenerator(cfg, self.traj.target, self.traj.rival, threads)
+        self.gen_prev = share.gen_prev if share else HostGenerator(cfg, self.traj.target, self.traj.rival, threads)
         self.prev_tables = None          # final planted tables of the step before
 
     def to_full(self, sub_pos: np.ndarray) -> np.ndarray:
