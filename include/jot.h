@@ -65,7 +65,8 @@ enum {
     JOT_ERR_HIP                 = -6,
     JOT_ERR_NO_DEVICE           = -7,
     JOT_ERR_NO_MEMORY           = -8,   /* host allocation failed */
-    JOT_ERR_WRONG_DEVICE        = -9    /* the current HIP device is not the one the state was created on */
+    JOT_ERR_WRONG_DEVICE        = -9,   /* the current HIP device is not the one the state was created on */
+    JOT_ERR_TOO_LARGE           = -10   /* jot_step_static: the problem does not fit the library's fixed scratch array */
 };
 
 typedef struct {
@@ -199,6 +200,32 @@ typedef struct {
 
 int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
                 const jot_step_options* opt, void* stream);
+
+/*
+ * One finalization pass that allocates nothing, for callers that cannot allocate: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  It is jot_step
+ * without a state object: the canvas comes in and goes out through the caller's arrays, and the
+ * working memory (partial results, counters, lists, the bit image of the mask) is a fixed array
+ * inside the library, JOT_STATIC_MAX_WORKSPACE bytes on every GPU the library runs on, held until
+ * the process ends.  No device or host memory is allocated or freed, no event is created, nothing
+ * is synchronised: the call only enqueues kernels on `stream`.
+ *   p              : as for jot_init_state; jot_workspace_bytes(p) must not exceed
+ *                    JOT_STATIC_MAX_WORKSPACE, else JOT_ERR_TOO_LARGE (about 26 000 canvas positions
+ *                    B*L; the vocabulary size does not matter)
+ *   logits_dev, stride_b, stride_l : as for jot_step
+ *   tokens_dev     : [B, L] int32, in and out: finalized positions receive their token
+ *   masked_dev     : [B, L] uint8, in and out: finalized positions are cleared
+ *   active_out_dev : [B*L] int32, out: the positions a next step would examine, ascending b*L+i
+ *   n_active_out_dev : int64, out: how many of them
+ * The step is numbered 1 (no state is carried from call to call).  Every call on a GPU uses that
+ * GPU's one array: calls that overlap on one GPU (different streams or threads) race, the caller
+ * must order them.  The first call on a device looks up the array's address and the launch shapes;
+ * make it outside stream capture.
+ */
+#define JOT_STATIC_MAX_WORKSPACE (4 << 20)
+int jot_step_static(const jot_params* p, const void* logits_dev, int64_t stride_b, int64_t stride_l,
+                    int32_t* tokens_dev, uint8_t* masked_dev, int32_t* active_out_dev,
+                    int64_t* n_active_out_dev, void* stream);
 
 /* Number of positions the NEXT step would examine (0 = decoding finished).  Waits for the work
  * enqueued so far on this state.  <0: JOT_ERR_*. */

@@ -11,7 +11,7 @@ import numpy as np
 __all__ = [
     "JOT_F32", "JOT_BF16", "JOT_CONF_RATIO", "JOT_CONF_MAXPROB", "JOT_CONF_PROBGAP",
     "JotParams", "JotError", "load_library", "library_path",
-    "jot_workspace_bytes", "jot_init_state", "jot_step", "jot_step_scheduled", "jot_step_sampled", "jot_step_ex", "JotStepOptions", "jot_last_flags", "jot_last_kl", "jot_last_gap", "jot_last_final_token", "jot_active_count", "jot_step_index",
+    "jot_workspace_bytes", "jot_init_state", "jot_step", "jot_step_scheduled", "jot_step_sampled", "jot_step_ex", "jot_step_static", "JOT_STATIC_MAX_WORKSPACE", "JotStepOptions", "jot_last_flags", "jot_last_kl", "jot_last_gap", "jot_last_final_token", "jot_active_count", "jot_step_index",
     "jot_anomaly_count", "jot_tokens", "jot_masked", "jot_commit_step", "jot_active_list",
     "jot_commit_log", "jot_examined_list", "jot_last_token", "jot_last_conf", "jot_last_p1",
     "jot_last_p2", "jot_last_tau", "jot_profile_enable", "jot_profile_read", "jot_release",
@@ -20,6 +20,7 @@ __all__ = [
 
 JOT_F32, JOT_BF16 = 0, 1
 JOT_CONF_RATIO, JOT_CONF_MAXPROB, JOT_CONF_PROBGAP = 0, 1, 2
+JOT_STATIC_MAX_WORKSPACE = 4 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "_lib", "libjot.so")
@@ -77,6 +78,7 @@ def load_library():
         "jot_step_scheduled": (ctypes.c_int, [vp, vp, i64, i64, vp, ctypes.c_float, vp]),
         "jot_step_sampled": (ctypes.c_int, [vp, vp, i64, i64, vp, ctypes.c_float, vp, vp]),
         "jot_step_ex": (ctypes.c_int, [vp, vp, i64, i64, ctypes.POINTER(JotStepOptions), vp]),
+        "jot_step_static": (ctypes.c_int, [pp, vp, i64, i64, vp, vp, vp, vp, vp]),
         "jot_last_flags": (vp, [vp]), "jot_last_kl": (vp, [vp]), "jot_last_gap": (vp, [vp]), "jot_last_final_token": (vp, [vp]),
         "jot_active_count": (i64, [vp]),
         "jot_step_index": (i32, [vp]),
@@ -144,6 +146,12 @@ def jot_step_ex(s: int, logits_dev: int, stride_b: int, stride_l: int, opt: "Jot
                 stream: int = 0) -> None:
     _check(load_library().jot_step_ex(s, logits_dev, stride_b, stride_l,
                                       ctypes.byref(opt) if opt is not None else None, stream), "jot_step_ex")
+
+
+def jot_step_static(p: JotParams, logits_dev: int, stride_b: int, stride_l: int, tokens_dev: int,
+                    masked_dev: int, active_out_dev: int, n_active_out_dev: int, stream: int = 0) -> None:
+    _check(load_library().jot_step_static(ctypes.byref(p), logits_dev, stride_b, stride_l, tokens_dev, masked_dev,
+                                          active_out_dev, n_active_out_dev, stream), "jot_step_static")
 
 
 def jot_active_count(s: int) -> int:

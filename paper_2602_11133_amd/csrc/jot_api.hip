@@ -5,8 +5,8 @@
 
 #include <hip/hip_runtime.h>
 #include <math.h>
+#include <mutex>
 #include <new>
-#include <stdlib.h>
 #include <string.h>
 
 #include "jot_compact.h"
@@ -17,6 +17,9 @@
 #include "jot_schedule.h"
 #include "jot_vocab_reduce.h"
 #include "jot_vocab_reduce_kl.h"
+
+// Working memory of jot_step_static() (see below): one fixed array per GPU.
+static __device__ __align__(256) unsigned char scratch[JOT_STATIC_MAX_WORKSPACE];
 
 namespace {
 
@@ -40,7 +43,7 @@ constexpr int kPerRowStepMax = 2048;   // longest per-row examined list handled 
 struct Layout {
     int64_t tokens, masked, commit_step, resolved_bits, active0, active1, counters, epoch, anomalies,
         partials, last_token, last_conf, last_p1, last_p2, last_tau, last_flags, last_m1, last_gap, last_final, lse, lse_step, last_kl, identity, sample_list, sample_count, row_block, row_n_active0, row_n_active1,
-        row_n_commit, commit_log, total;
+        row_n_commit, commit_log, host_block, total;
     int64_t n_partials;
     int32_t words_per_row;
 };
@@ -102,6 +105,7 @@ Layout make_layout(const jot_params* p, int target_items)
     l.row_n_active1 = take((int64_t)p->B * 4);
     l.row_n_commit = take((int64_t)p->B * 4);
     l.commit_log = take(n * 12);
+    l.host_block = take(sizeof(JotHostBlock));   // where a state without pinned host memory sends its counters
     l.total = off;
     return l;
 }
@@ -129,6 +133,7 @@ struct jot_state {
     hipEvent_t done;
     bool have_done;
     bool per_row_step;          // decision + schedule + row counts in one per-row launch
+    bool host_resources;        // owns pinned host counters and events (false: a transient state on the caller's stack)
     bool profile;
     hipEvent_t prof0[JOT_PROFILE_RING], prof1[JOT_PROFILE_RING];
     int32_t prof_step[JOT_PROFILE_RING];    // step recorded in each ring slot, 0 = none
@@ -184,7 +189,9 @@ int enqueue_compaction(jot_state* s, bool creating, hipStream_t st, bool count_r
     // The kernel above also wrote the new counters into pinned host memory.  Outside stream
     // capture the host waits on an event recorded here; a captured step may be replayed any number
     // of times later, so after one the host waits for the whole device instead.
-    if (stream_is_capturing(st)) {
+    if (!s->host_resources) {
+        // transient state: nothing on the host waits for it
+    } else if (stream_is_capturing(st)) {
         s->sync_device = true;
     } else {
         if (hipEventRecord(s->done, st) != hipSuccess) return JOT_ERR_HIP;
@@ -205,66 +212,100 @@ int wait_done(jot_state* s)
     return JOT_OK;
 }
 
-}  // namespace
+// Working memory of jot_step_static(): one fixed array per GPU, held until the process ends.
+// In host code the array's name is only a handle; its address on a device comes from
+// hipGetSymbolAddress, asked once per device with that device current.
+constexpr int64_t kStaticScratchBytes = JOT_STATIC_MAX_WORKSPACE;
+void* g_scratch_ptr[64];
+std::mutex g_scratch_mutex;
 
-extern "C" {
-
-int64_t jot_workspace_bytes(const jot_params* p)
+int scratch_address(int dev, char** out)
 {
-    const int rc = validate(p);
-    if (rc != JOT_OK) return rc;
-    return make_layout(p, max_target_items()).total;
+    if (dev < 0 || dev >= 64) return JOT_ERR_NO_DEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return JOT_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = static_cast<char*>(g_scratch_ptr[dev]);
+    return JOT_OK;
 }
 
-int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, int64_t workspace_bytes,
-                   const int32_t* tokens_dev, const uint8_t* masked_dev, void* stream)
+// Results of a transient state, copied from its workspace into the caller's arrays.
+__global__ __launch_bounds__(JOT_WG) void jot_copy_out_kernel(
+    int64_t n, JotFrame frame, const int32_t* __restrict__ tokens, const uint8_t* __restrict__ masked,
+    int32_t* __restrict__ tokens_out, uint8_t* __restrict__ masked_out, int32_t* __restrict__ active_out,
+    int64_t* __restrict__ n_active_out)
 {
-    if (!out) return JOT_ERR_NULL_POINTER;
-    *out = nullptr;
-    const int rc = validate(p);
-    if (rc != JOT_OK) return rc;
-    if (!workspace_dev || !tokens_dev || !masked_dev) return JOT_ERR_NULL_POINTER;
-    if (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign) return JOT_ERR_MISALIGNED;
-    if (reinterpret_cast<uintptr_t>(tokens_dev) % 4) return JOT_ERR_MISALIGNED;
-    if (workspace_bytes < make_layout(p, max_target_items()).total) return JOT_ERR_WORKSPACE_TOO_SMALL;
+    const int half = frame.epoch->parity;                 // the half the NEXT step would read
+    const int64_t n_active = frame.counters[half]->n_active;
+    const int32_t* __restrict__ active = frame.active[half];
+    for (int64_t k = (int64_t)blockIdx.x * JOT_WG + threadIdx.x; k < n; k += (int64_t)gridDim.x * JOT_WG) {
+        tokens_out[k] = tokens[k];
+        masked_out[k] = masked[k];
+        if (k < n_active) active_out[k] = active[k];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) *n_active_out = n_active;
+}
 
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return JOT_ERR_NO_DEVICE;
-    int cus = 0;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-        cus = kFallbackCus;
-    if (cus > 2048) cus = 2048;
+// Launch shapes of a device, queried once per device and logit type.
+struct DeviceShape {
+    bool known;
+    int cus;
+    int occ[2], occ_kl[2];      // resident workgroups per CU of the two reductions, by jot_dtype
+};
+constexpr int kMaxDevices = 64;
+DeviceShape g_shape[kMaxDevices];
+std::mutex g_shape_mutex;
 
-    jot_state* s = new (std::nothrow) jot_state();
-    if (!s) return JOT_ERR_NO_MEMORY;
+int occupancy_of(const void* kernel, int wg)
+{
+    int occ = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, wg, 0) != hipSuccess || occ < 1) {
+        (void)hipGetLastError();
+        occ = kDefaultWgPerCu;
+    }
+    return occ > kMaxWgPerCu ? kMaxWgPerCu : occ;
+}
+
+DeviceShape shape_of(int dev)
+{
+    std::lock_guard<std::mutex> lock(g_shape_mutex);
+    DeviceShape local;
+    DeviceShape& d = (dev >= 0 && dev < kMaxDevices) ? g_shape[dev] : local;
+    if (dev < 0 || dev >= kMaxDevices) d.known = false;
+    if (!d.known) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = kFallbackCus;
+        d.cus = cus > 2048 ? 2048 : cus;
+        // persistent grids = exactly the workgroups that can be resident at once
+        d.occ[JOT_F32] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotF32>), JotF32::WG);
+        d.occ[JOT_BF16] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotBF16>), JotBF16::WG);
+        // the reduction with the stability term has its own register footprint, hence its own grid
+        d.occ_kl[JOT_F32] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kl_kernel<JotF32KL>), JotF32KL::WG);
+        d.occ_kl[JOT_BF16] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kl_kernel<JotBF16KL>), JotBF16KL::WG);
+        d.known = true;
+    }
+    return d;
+}
+
+// Everything of a state that follows from the parameters, the device and the workspace address.
+void configure(jot_state* s, const jot_params* p, int dev, char* ws)
+{
+    const DeviceShape shape = shape_of(dev);
     s->p = *p;
     s->device = dev;
-    s->ws = static_cast<char*>(workspace_dev);
-    // persistent grid = exactly the workgroups that can be resident at once
-    int occ = 0;
-    const void* kfn = p->dtype == JOT_F32 ? reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotF32>)
-                                          : reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotBF16>);
-    const int reduce_wg = p->dtype == JOT_F32 ? JotF32::WG : JotBF16::WG;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kfn, reduce_wg, 0) != hipSuccess || occ < 1)
-        occ = kDefaultWgPerCu;
-    if (occ > kMaxWgPerCu) occ = kMaxWgPerCu;
-    if (const char* e = getenv("JOT_REDUCE_WG_PER_CU")) {        // tuning aid, 1..16
-        const int v = atoi(e);
-        if (v >= 1 && v <= kMaxWgPerCu) occ = v;
-    }
-    s->grid_reduce = cus * occ;
-    {   // the reduction with the stability term has its own register footprint, hence its own grid
-        int occ_kl = 0;
-        const void* kfn_kl = p->dtype == JOT_F32 ? reinterpret_cast<const void*>(jot_vocab_reduce_kl_kernel<JotF32KL>)
-                                                 : reinterpret_cast<const void*>(jot_vocab_reduce_kl_kernel<JotBF16KL>);
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ_kl, kfn_kl, p->dtype == JOT_F32 ? JotF32KL::WG : JotBF16KL::WG, 0) != hipSuccess || occ_kl < 1)
-            occ_kl = kDefaultWgPerCu;
-        if (occ_kl > kMaxWgPerCu) occ_kl = kMaxWgPerCu;
-        s->grid_reduce_kl = cus * occ_kl;
-        s->target_items_kl = s->grid_reduce_kl * kItemsPerWg;
-        if (s->target_items_kl > max_target_items()) s->target_items_kl = max_target_items();
-    }
-    s->grid_sample = cus * 4;
+    s->ws = ws;
+    s->grid_reduce = shape.cus * shape.occ[p->dtype];
+    s->grid_reduce_kl = shape.cus * shape.occ_kl[p->dtype];
+    s->target_items_kl = s->grid_reduce_kl * kItemsPerWg;
+    if (s->target_items_kl > max_target_items()) s->target_items_kl = max_target_items();
+    s->grid_sample = shape.cus * 4;
     s->target_items = s->grid_reduce * kItemsPerWg;
     if (s->target_items > max_target_items()) s->target_items = max_target_items();
     s->lay = make_layout(p, max_target_items());
@@ -282,7 +323,9 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
     }
     s->have_done = false;
     s->profile = false;
+    s->host_resources = false;
     s->host = nullptr;
+    s->host_dev = s->at<HostCounters>(s->lay.host_block);     // replaced by pinned host memory if the state owns some
 
     JotDecideParams& d = s->decide;
     memset(&d, 0, sizeof d);
@@ -302,76 +345,32 @@ int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, in
     s->compact.B = p->B; s->compact.L = p->L;
     s->compact.gen_start = p->gen_start; s->compact.block_size = p->block_size;
     s->compact.words_per_row = s->lay.words_per_row;
+}
 
-    if (hipHostMalloc(reinterpret_cast<void**>(&s->host), sizeof(HostCounters), hipHostMallocMapped) != hipSuccess) {
-        delete s;
-        return JOT_ERR_HIP;
-    }
-    memset(s->host, 0, sizeof(HostCounters));
-    if (hipHostGetDevicePointer(reinterpret_cast<void**>(&s->host_dev), s->host, 0) != hipSuccess) {
-        (void)hipHostFree(s->host);
-        delete s;
-        return JOT_ERR_HIP;
-    }
-    if (hipEventCreateWithFlags(&s->done, hipEventDisableTiming) != hipSuccess) {
-        (void)hipHostFree(s->host);
-        delete s;
-        return JOT_ERR_HIP;
-    }
-
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int64_t n = (int64_t)p->B * p->L;
+// Copies the caller's canvas into the workspace and builds the first examined list.
+int enqueue_init(jot_state* s, const int32_t* tokens_dev, const uint8_t* masked_dev, hipStream_t st)
+{
+    const int64_t n = (int64_t)s->p.B * s->p.L;
     hipLaunchKernelGGL(jot_init_copy_kernel, dim3((unsigned)((n + JOT_WG - 1) / JOT_WG)), dim3(JOT_WG), 0, st,
                        n, tokens_dev, masked_dev, s->at<int32_t>(s->lay.tokens),
                        s->at<uint8_t>(s->lay.masked), s->at<int32_t>(s->lay.commit_step),
                        s->counters(0), s->at<unsigned long long>(s->lay.anomalies), s->frame.epoch,
                        s->at<int32_t>(s->lay.lse_step), s->at<int32_t>(s->lay.identity));
-    int rc2 = (hipGetLastError() == hipSuccess) ? enqueue_compaction(s, /*creating=*/true, st, true) : JOT_ERR_HIP;
-    if (rc2 == JOT_OK && hipStreamSynchronize(st) != hipSuccess) rc2 = JOT_ERR_HIP;
-    if (rc2 != JOT_OK) {
-        jot_release(s);
-        return rc2;
-    }
-    *out = s;
-    return JOT_OK;
+    if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
+    return enqueue_compaction(s, /*creating=*/true, st, true);
 }
 
-int jot_step(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l, void* stream)
+// Host-side checks of one step's arguments (no device work).
+int validate_step(const jot_params& p, const void* logits_dev, int64_t stride_b, int64_t stride_l,
+                  const jot_step_options* opt)
 {
-    return jot_step_scheduled(s, logits_dev, stride_b, stride_l, nullptr, 0.0f, stream);
-}
-
-int jot_step_scheduled(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
-                       const int32_t* n_transfer_dev, float transfer_frac, void* stream)
-{
-    return jot_step_sampled(s, logits_dev, stride_b, stride_l, n_transfer_dev, transfer_frac, nullptr, stream);
-}
-
-int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
-                     const int32_t* n_transfer_dev, float transfer_frac, const float* uniforms_dev,
-                     void* stream)
-{
-    jot_step_options opt;
-    memset(&opt, 0, sizeof opt);
-    opt.n_transfer_dev = n_transfer_dev;
-    opt.transfer_frac = transfer_frac;
-    opt.uniforms_dev = uniforms_dev;
-    return jot_step_ex(s, logits_dev, stride_b, stride_l, &opt, stream);
-}
-
-int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
-                const jot_step_options* opt, void* stream)
-{
-    jot_step_options none;
-    memset(&none, 0, sizeof none);
-    if (!opt) opt = &none;
     const int32_t* n_transfer_dev = opt->n_transfer_dev;
     const float transfer_frac = opt->transfer_frac;
     const float* uniforms_dev = opt->uniforms_dev;
     const bool do_rowwide = opt->enable_global_gap != 0;
     const bool do_kl = opt->enable_kl != 0;
     const bool compact = opt->logits_compact != 0;
-    if (!s || !logits_dev) return JOT_ERR_NULL_POINTER;
+    if (!logits_dev) return JOT_ERR_NULL_POINTER;
     if (compact && do_kl) return JOT_ERR_INVALID_ARG;     // the previous step's rows are in another order
     if (do_kl) {
         if (!opt->prev_logits_dev) return JOT_ERR_NULL_POINTER;
@@ -381,12 +380,8 @@ int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t 
     }
     if (do_rowwide && !isfinite(opt->global_gap)) return JOT_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(uniforms_dev) % 4) return JOT_ERR_MISALIGNED;
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess) return JOT_ERR_NO_DEVICE;
-    if (dev != s->device) return JOT_ERR_WRONG_DEVICE;
     if (!(transfer_frac >= 0.0f && transfer_frac <= 1.0f)) return JOT_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(n_transfer_dev) % 4) return JOT_ERR_MISALIGNED;
-    const jot_params& p = s->p;
     const int64_t esz = p.dtype == JOT_F32 ? 4 : 2;
     if (stride_l < p.V) return JOT_ERR_INVALID_ARG;
     if (!compact) {
@@ -396,6 +391,20 @@ int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t 
     if (reinterpret_cast<uintptr_t>(logits_dev) % 16 || (stride_l * esz) % 16 ||
         (!compact && p.B > 1 && (stride_b * esz) % 16))
         return JOT_ERR_MISALIGNED;
+    return JOT_OK;
+}
+
+// The launch sequence of one step; arguments already validated.
+int enqueue_step(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
+                 const jot_step_options* opt, hipStream_t st)
+{
+    const jot_params& p = s->p;
+    const int32_t* n_transfer_dev = opt->n_transfer_dev;
+    const float transfer_frac = opt->transfer_frac;
+    const float* uniforms_dev = opt->uniforms_dev;
+    const bool do_rowwide = opt->enable_global_gap != 0;
+    const bool do_kl = opt->enable_kl != 0;
+    const bool compact = opt->logits_compact != 0;
     // A compact tensor has one row per examined entry.  The reduction is handed the identity list
     // and a canvas length no position reaches, so that "position" r resolves to row r of batch 0.
     JotFrame reduce_frame = s->frame;
@@ -405,7 +414,6 @@ int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t 
         reduce_L = 0x7fffffff;
     }
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
     const int32_t step = s->step + 1;           // host-side call count; the kernels use the device epoch
     const int64_t n = (int64_t)p.B * p.L;
     const bool capturing = stream_is_capturing(st);
@@ -521,6 +529,137 @@ int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t 
     return enqueue_compaction(s, /*creating=*/false, st, /*count_rows=*/!s->per_row_step, /*write_rows=*/!one_launch);
 }
 
+}  // namespace
+
+extern "C" {
+
+int64_t jot_workspace_bytes(const jot_params* p)
+{
+    const int rc = validate(p);
+    if (rc != JOT_OK) return rc;
+    return make_layout(p, max_target_items()).total;
+}
+
+int jot_init_state(jot_state** out, const jot_params* p, void* workspace_dev, int64_t workspace_bytes,
+                   const int32_t* tokens_dev, const uint8_t* masked_dev, void* stream)
+{
+    if (!out) return JOT_ERR_NULL_POINTER;
+    *out = nullptr;
+    const int rc = validate(p);
+    if (rc != JOT_OK) return rc;
+    if (!workspace_dev || !tokens_dev || !masked_dev) return JOT_ERR_NULL_POINTER;
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign) return JOT_ERR_MISALIGNED;
+    if (reinterpret_cast<uintptr_t>(tokens_dev) % 4) return JOT_ERR_MISALIGNED;
+    if (workspace_bytes < make_layout(p, max_target_items()).total) return JOT_ERR_WORKSPACE_TOO_SMALL;
+
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return JOT_ERR_NO_DEVICE;
+
+    jot_state* s = new (std::nothrow) jot_state();
+    if (!s) return JOT_ERR_NO_MEMORY;
+    configure(s, p, dev, static_cast<char*>(workspace_dev));
+    s->host_resources = true;
+
+    if (hipHostMalloc(reinterpret_cast<void**>(&s->host), sizeof(HostCounters), hipHostMallocMapped) != hipSuccess) {
+        delete s;
+        return JOT_ERR_HIP;
+    }
+    memset(s->host, 0, sizeof(HostCounters));
+    if (hipHostGetDevicePointer(reinterpret_cast<void**>(&s->host_dev), s->host, 0) != hipSuccess) {
+        (void)hipHostFree(s->host);
+        delete s;
+        return JOT_ERR_HIP;
+    }
+    if (hipEventCreateWithFlags(&s->done, hipEventDisableTiming) != hipSuccess) {
+        (void)hipHostFree(s->host);
+        delete s;
+        return JOT_ERR_HIP;
+    }
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc2 = enqueue_init(s, tokens_dev, masked_dev, st);
+    if (rc2 == JOT_OK && hipStreamSynchronize(st) != hipSuccess) rc2 = JOT_ERR_HIP;
+    if (rc2 != JOT_OK) {
+        jot_release(s);
+        return rc2;
+    }
+    *out = s;
+    return JOT_OK;
+}
+
+int jot_step(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l, void* stream)
+{
+    return jot_step_scheduled(s, logits_dev, stride_b, stride_l, nullptr, 0.0f, stream);
+}
+
+int jot_step_scheduled(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
+                       const int32_t* n_transfer_dev, float transfer_frac, void* stream)
+{
+    return jot_step_sampled(s, logits_dev, stride_b, stride_l, n_transfer_dev, transfer_frac, nullptr, stream);
+}
+
+int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
+                     const int32_t* n_transfer_dev, float transfer_frac, const float* uniforms_dev,
+                     void* stream)
+{
+    jot_step_options opt;
+    memset(&opt, 0, sizeof opt);
+    opt.n_transfer_dev = n_transfer_dev;
+    opt.transfer_frac = transfer_frac;
+    opt.uniforms_dev = uniforms_dev;
+    return jot_step_ex(s, logits_dev, stride_b, stride_l, &opt, stream);
+}
+
+int jot_step_ex(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
+                const jot_step_options* opt, void* stream)
+{
+    jot_step_options none;
+    memset(&none, 0, sizeof none);
+    if (!opt) opt = &none;
+    if (!s) return JOT_ERR_NULL_POINTER;
+    const int rc = validate_step(s->p, logits_dev, stride_b, stride_l, opt);
+    if (rc != JOT_OK) return rc;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return JOT_ERR_NO_DEVICE;
+    if (dev != s->device) return JOT_ERR_WRONG_DEVICE;
+    return enqueue_step(s, logits_dev, stride_b, stride_l, opt, static_cast<hipStream_t>(stream));
+}
+
+int jot_step_static(const jot_params* p, const void* logits_dev, int64_t stride_b, int64_t stride_l,
+                    int32_t* tokens_dev, uint8_t* masked_dev, int32_t* active_out_dev, int64_t* n_active_out_dev,
+                    void* stream)
+{
+    const int rc = validate(p);
+    if (rc != JOT_OK) return rc;
+    if (!tokens_dev || !masked_dev || !active_out_dev || !n_active_out_dev) return JOT_ERR_NULL_POINTER;
+    if (reinterpret_cast<uintptr_t>(tokens_dev) % 4 || reinterpret_cast<uintptr_t>(active_out_dev) % 4 ||
+        reinterpret_cast<uintptr_t>(n_active_out_dev) % 8)
+        return JOT_ERR_MISALIGNED;
+    jot_step_options none;
+    memset(&none, 0, sizeof none);
+    const int rc1 = validate_step(*p, logits_dev, stride_b, stride_l, &none);
+    if (rc1 != JOT_OK) return rc1;
+    if (make_layout(p, max_target_items()).total > kStaticScratchBytes) return JOT_ERR_TOO_LARGE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return JOT_ERR_NO_DEVICE;
+    char* ws = nullptr;
+    const int rc2 = scratch_address(dev, &ws);
+    if (rc2 != JOT_OK) return rc2;
+
+    jot_state t;                      // transient: lives for this call only, owns nothing
+    configure(&t, p, dev, ws);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc3 = enqueue_init(&t, tokens_dev, masked_dev, st);
+    if (rc3 == JOT_OK) rc3 = enqueue_step(&t, logits_dev, stride_b, stride_l, &none, st);
+    if (rc3 != JOT_OK) return rc3;
+    const int64_t n = (int64_t)p->B * p->L;
+    const unsigned grid = (unsigned)((n + JOT_WG - 1) / JOT_WG);
+    hipLaunchKernelGGL(jot_copy_out_kernel, dim3(grid), dim3(JOT_WG), 0, st, n, t.frame,
+                       t.at<int32_t>(t.lay.tokens), t.at<uint8_t>(t.lay.masked), tokens_dev, masked_dev,
+                       active_out_dev, n_active_out_dev);
+    return hipGetLastError() == hipSuccess ? JOT_OK : JOT_ERR_HIP;
+}
+
 int64_t jot_active_count(jot_state* s)
 {
     const int rc = wait_done(s);
@@ -622,6 +761,7 @@ const char* jot_strerror(int code)
     case JOT_ERR_NO_DEVICE: return "no HIP device";
     case JOT_ERR_NO_MEMORY: return "out of host memory";
     case JOT_ERR_WRONG_DEVICE: return "state belongs to another HIP device";
+    case JOT_ERR_TOO_LARGE: return "problem needs more working memory than the library's fixed scratch array holds";
     default: return "unknown error";
     }
 }
