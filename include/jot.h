@@ -44,7 +44,7 @@
 extern "C" {
 #endif
 
-typedef struct jot_state jot_state;      /* opaque, host memory, created by jot_init_state */
+typedef struct jot_state jot_state;      /* opaque, host memory, created by jot_init_state, freed by jot_release */
 
 typedef enum { JOT_F32 = 0, JOT_BF16 = 1 } jot_dtype;
 
@@ -145,8 +145,9 @@ int jot_step_scheduled(jot_state* s, const void* logits_dev, int64_t stride_b, i
  *   uniforms_dev : [B, L] float DEVICE array of numbers in [0, 1), drawn by the caller for this
  *                  step; read only at finalized positions.  NULL = argmax finalization.
  * Rows finalized in this step are read a second time (once per position over a whole decode).
- * If rounding keeps the cumulative sum from exceeding the uniform number (a number within
- * rounding of 1), the argmax token is kept.
+ * If the cumulative sum never exceeds the uniform number (a number within rounding of 1, or one
+ * that is not below 1), the token is the last one with a non-zero probability: the cumulative
+ * probability reaches 1 there.
  */
 int jot_step_sampled(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t stride_l,
                      const int32_t* n_transfer_dev, float transfer_frac, const float* uniforms_dev,
@@ -227,12 +228,26 @@ int jot_step_static(const jot_params* p, const void* logits_dev, int64_t stride_
                     int32_t* tokens_dev, uint8_t* masked_dev, int32_t* active_out_dev,
                     int64_t* n_active_out_dev, void* stream);
 
-/* Number of positions the NEXT step would examine (0 = decoding finished).  Waits for the work
- * enqueued so far on this state.  <0: JOT_ERR_*. */
+/* Algorithm 1's loop test: the size of the masked set M_n the NEXT step would examine (0 = decoding
+ * finished; in block mode, the masked positions of the current blocks).  Waits for the work enqueued
+ * so far on this state.  <0: JOT_ERR_*. */
 int64_t jot_active_count(jot_state* s);
 
-/* Number of jot_step calls so far (host counter, no synchronisation). */
-int32_t jot_step_index(const jot_state* s);
+/* The same number without waiting: the count stored by the last step that has COMPLETED on the
+ * device, and in *steps_done (may be NULL) how many steps have completed.  A decode loop can enqueue
+ * the next forward pass, poll this until *steps_done reaches the number of steps it has enqueued, and
+ * so overlap the test with other work.  Never blocks on the device. */
+int64_t jot_active_count_poll(const jot_state* s, int32_t* steps_done);
+
+/* After steps that were enqueued under stream capture (and are replayed as a HIP graph on a stream
+ * the library never saw), the waiting calls above wait for the whole device.  Tell the library which
+ * stream the replays run on: it records an event there (not under capture) and the waiting calls
+ * wait for that event instead.  Call it after each replay whose results are to be read. */
+int jot_wait_on_stream(jot_state* s, void* stream);
+
+/* Number of steps completed on this state (n of Algorithm 1's loop), counted on the device, so it is
+ * right for steps replayed from a captured graph as well.  Waits like jot_active_count. */
+int32_t jot_step_index(jot_state* s);
 
 /* Rows skipped so far because they had no softmax.  Waits like jot_active_count. */
 int64_t jot_anomaly_count(jot_state* s);
@@ -241,20 +256,25 @@ int64_t jot_anomaly_count(jot_state* s);
  * Device views into the workspace.  Pointers stay valid until the workspace is freed; the
  * contents are those of the last enqueued step once its stream work has completed.
  */
-const int32_t* jot_tokens(const jot_state* s);        /* [B, L] current canvas                        */
-const uint8_t* jot_masked(const jot_state* s);        /* [B, L] 1 = still masked                      */
-const int32_t* jot_commit_step(const jot_state* s);   /* [B, L] step at which finalized, 0 = not (yet) */
-const int32_t* jot_active_list(jot_state* s);         /* [jot_active_count] ascending b*L+i, next step;
-                                                         waits like jot_active_count (the list is double
-                                                         buffered; which half is current is device state) */
-/* Finalizations in order: triples (step, b*L+i, token), steps non-decreasing, positions
- * ascending within a step.  *n receives the number of triples (waits like jot_active_count). */
+const int32_t* jot_tokens(const jot_state* s);        /* [B, L] the canvas x of Algorithm 1           */
+const uint8_t* jot_masked(const jot_state* s);        /* [B, L] 1 = still [M] (membership in M_n)     */
+const int32_t* jot_commit_step(const jot_state* s);   /* [B, L] step n at which Eq. 6 (or an optional
+                                                         rule) finalized the position, 0 = not (yet)  */
+/* Algorithm 1's masked set M_n for the next step, as a list: [jot_active_count] ascending b*L+i
+ * (in block mode restricted to the current blocks, Section 4.2).  Waits like jot_active_count (the
+ * list is double buffered; which half is current is device state). */
+const int32_t* jot_active_list(jot_state* s);
+/* Every finalization (Eq. 6: x^i <- argmax, i leaves M; or a token chosen by an optional rule) in
+ * order: triples (step, b*L+i, token), steps non-decreasing, positions ascending within a step.
+ * *n receives the number of triples (waits like jot_active_count). */
 const int32_t* jot_commit_log(jot_state* s, int64_t* n);
 
 /*
  * Per-position results of the LAST step, aligned with the list that step examined
  * (jot_examined_list, length *n = number of examined positions; waits like jot_active_count):
- * token = argmax, conf, p1, p2, tau = tau_i.  For rows without a softmax conf is NaN.
+ * token = argmax_v pi_v and p1, p2 = the two largest probabilities (Section 4.1, Confidence Metric),
+ * conf = the confidence of Eq. 2 (or the selected other signal), tau = tau_i of Eq. 5 (from w of
+ * Eq. 3 and phi of Eq. 4).  For rows without a softmax conf is NaN.
  */
 const int32_t* jot_examined_list(jot_state* s, int64_t* n);
 const int32_t* jot_last_token(const jot_state* s);

@@ -119,8 +119,9 @@ int jot_oracle_softmax_row(const void *row, int dtype, int32_t V, double *pi)
  * Sampling-based finalization (Section 4.1, "Early-Exit Decision": the finalized token may be
  * sampled from pi instead of taking the argmax).  Inverse-CDF sampling with a uniform number u
  * in [0, 1) supplied by the caller: the token is the first index v whose cumulative probability
- * pi_0 + ... + pi_v exceeds u.  If rounding leaves the total just below u, the last index with a
- * non-zero probability is returned.  Also reports the cumulative probability just below and
+ * pi_0 + ... + pi_v exceeds u.  The cumulative probability reaches 1 at the last index with a
+ * non-zero probability: that index is returned for u >= 1 (not a valid draw, but defined), and
+ * also if rounding leaves the total just below u.  Also reports the cumulative probability just below and
  * just above the chosen token (so a test can tell how far u is from either edge).
  * Returns -1 for a row without a softmax.
  */
@@ -137,7 +138,7 @@ int32_t jot_oracle_sample_row(const void *row, int dtype, int32_t V, double u,
         double pv = exp(widen(row, dtype, v) - m1) / S;
         if (pv > 0.0)
             last = v;
-        if (cum + pv > u) {
+        if (u < 1.0 && cum + pv > u) {
             *cdf_below = cum;
             *cdf_above = cum + pv;
             return v;

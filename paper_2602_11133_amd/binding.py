@@ -11,7 +11,7 @@ import numpy as np
 __all__ = [
     "JOT_F32", "JOT_BF16", "JOT_CONF_RATIO", "JOT_CONF_MAXPROB", "JOT_CONF_PROBGAP",
     "JotParams", "JotError", "load_library", "library_path",
-    "jot_workspace_bytes", "jot_init_state", "jot_step", "jot_step_scheduled", "jot_step_sampled", "jot_step_ex", "jot_step_static", "JOT_STATIC_MAX_WORKSPACE", "JotStepOptions", "jot_last_flags", "jot_last_kl", "jot_last_gap", "jot_last_final_token", "jot_active_count", "jot_step_index",
+    "jot_workspace_bytes", "jot_init_state", "jot_step", "jot_step_scheduled", "jot_step_sampled", "jot_step_ex", "jot_step_static", "JOT_STATIC_MAX_WORKSPACE", "JotStepOptions", "jot_last_flags", "jot_last_kl", "jot_last_gap", "jot_last_final_token", "jot_active_count", "jot_active_count_poll", "jot_wait_on_stream", "jot_step_index",
     "jot_anomaly_count", "jot_tokens", "jot_masked", "jot_commit_step", "jot_active_list",
     "jot_commit_log", "jot_examined_list", "jot_last_token", "jot_last_conf", "jot_last_p1",
     "jot_last_p2", "jot_last_tau", "jot_profile_enable", "jot_profile_read", "jot_release",
@@ -81,6 +81,8 @@ def load_library():
         "jot_step_static": (ctypes.c_int, [pp, vp, i64, i64, vp, vp, vp, vp, vp]),
         "jot_last_flags": (vp, [vp]), "jot_last_kl": (vp, [vp]), "jot_last_gap": (vp, [vp]), "jot_last_final_token": (vp, [vp]),
         "jot_active_count": (i64, [vp]),
+        "jot_active_count_poll": (i64, [vp, ctypes.POINTER(i32)]),
+        "jot_wait_on_stream": (ctypes.c_int, [vp, vp]),
         "jot_step_index": (i32, [vp]),
         "jot_anomaly_count": (i64, [vp]),
         "jot_tokens": (vp, [vp]), "jot_masked": (vp, [vp]), "jot_commit_step": (vp, [vp]),
@@ -156,6 +158,17 @@ def jot_step_static(p: JotParams, logits_dev: int, stride_b: int, stride_l: int,
 
 def jot_active_count(s: int) -> int:
     return _check(load_library().jot_active_count(s), "jot_active_count")
+
+
+def jot_active_count_poll(s: int):
+    """(count stored by the last completed step, number of completed steps); never waits."""
+    done = ctypes.c_int32()
+    n = _check(load_library().jot_active_count_poll(s, ctypes.byref(done)), "jot_active_count_poll")
+    return n, done.value
+
+
+def jot_wait_on_stream(s: int, stream: int) -> None:
+    _check(load_library().jot_wait_on_stream(s, stream), "jot_wait_on_stream")
 
 
 def jot_step_index(s: int) -> int:

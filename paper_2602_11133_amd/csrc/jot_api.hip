@@ -666,7 +666,42 @@ int64_t jot_active_count(jot_state* s)
     return rc != JOT_OK ? rc : s->host->c.n_active;
 }
 
-int32_t jot_step_index(const jot_state* s) { return s ? s->step : JOT_ERR_NULL_POINTER; }
+int32_t jot_step_index(jot_state* s)
+{
+    const int rc = wait_done(s);
+    return rc != JOT_OK ? rc : s->host->steps_done;     // counted on the device: right under graph replay too
+}
+
+int64_t jot_active_count_poll(const jot_state* s, int32_t* steps_done)
+{
+    if (!s) return JOT_ERR_NULL_POINTER;
+    // The closing workgroup of a step stores `begin`, then the counters, then `steps_done`, with
+    // system-scope fences between: a snapshot is consistent if steps_done (read first) equals
+    // begin (read last).  Otherwise a store is in flight: try again.
+    const volatile HostCounters* h = s->host;
+    for (int tries = 0; tries < 100000; ++tries) {
+        const int32_t end = h->steps_done;
+        __atomic_thread_fence(__ATOMIC_ACQUIRE);
+        const int64_t n = h->c.n_active;
+        __atomic_thread_fence(__ATOMIC_ACQUIRE);
+        if (h->begin == end) {
+            if (steps_done) *steps_done = end;
+            return n;
+        }
+    }
+    return JOT_ERR_HIP;
+}
+
+int jot_wait_on_stream(jot_state* s, void* stream)
+{
+    if (!s) return JOT_ERR_NULL_POINTER;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (stream_is_capturing(st)) return JOT_ERR_INVALID_ARG;
+    if (hipEventRecord(s->done, st) != hipSuccess) return JOT_ERR_HIP;
+    s->have_done = true;
+    s->sync_device = false;
+    return JOT_OK;
+}
 
 int64_t jot_anomaly_count(jot_state* s)
 {
@@ -711,10 +746,19 @@ int jot_profile_enable(jot_state* s, int on)
 {
     if (!s) return JOT_ERR_NULL_POINTER;
     if (on && !s->profile) {
+        int made = 0;                       // events created so far (prof0[k] before prof1[k])
         for (int k = 0; k < JOT_PROFILE_RING; ++k) {
             s->prof_step[k] = 0;
-            if (hipEventCreate(&s->prof0[k]) != hipSuccess || hipEventCreate(&s->prof1[k]) != hipSuccess)
-                return JOT_ERR_HIP;
+            if (hipEventCreate(&s->prof0[k]) != hipSuccess) break;
+            ++made;
+            if (hipEventCreate(&s->prof1[k]) != hipSuccess) break;
+            ++made;
+        }
+        if (made != 2 * JOT_PROFILE_RING) {     // give back what was created
+            for (int k = 0; k < made; ++k)
+                (void)hipEventDestroy((k & 1) ? s->prof1[k >> 1] : s->prof0[k >> 1]);
+            (void)hipGetLastError();
+            return JOT_ERR_HIP;
         }
         s->profile = true;
     } else if (!on && s->profile) {

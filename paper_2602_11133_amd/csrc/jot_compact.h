@@ -195,15 +195,18 @@ __device__ __forceinline__ void jot_row_write(const JotCompactParams& prm, const
         const uint32_t arrived = atomicAdd(&frame.epoch->rows_done, 1u);
         if (arrived == (uint32_t)prm.B - 1u) {
             __threadfence();
+            const int32_t done = frame.epoch->steps_done + (creating ? 0 : 1);
+            io.host_out->begin = done;
+            __threadfence_system();
             // device-scope loads: the numbers were written by the workgroup of the last row
             io.host_out->c.n_active = __hip_atomic_load(&cnt_out->n_active, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             io.host_out->c.n_log = __hip_atomic_load(&cnt_out->n_log, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             io.host_out->c.n_examined = __hip_atomic_load(&cnt_out->n_examined, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             io.host_out->c.reserved = 0;
             io.host_out->anomalies = __hip_atomic_load(io.anomalies, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int32_t done = frame.epoch->steps_done + (creating ? 0 : 1);
-            io.host_out->steps_done = done;
             io.host_out->parity = half ^ 1;
+            __threadfence_system();
+            io.host_out->steps_done = done;
             *io.sample_count = 0;         // the sampling work list of this step has been consumed
             frame.epoch->rows_done = 0u;
             frame.epoch->steps_done = done;

@@ -77,11 +77,15 @@ struct JotFrame {
 };
 
 // Block the last compaction workgroup writes into host-visible pinned memory.
+// Written in the order: begin, (fence), everything else, (fence), steps_done -- so a host reader
+// that finds begin == steps_done around its reads has a consistent snapshot of that step.
 struct JotHostBlock {
     JotCounters c;
     unsigned long long anomalies;
     int32_t steps_done;
     int32_t parity;       // half that the NEXT step reads (= where the current examined list is)
+    int32_t begin;        // number of the step whose results are being (or have been) stored
+    int32_t pad;
 };
 
 #define JOT_LOG2E 1.44269504088896340736f

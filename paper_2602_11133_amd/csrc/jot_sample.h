@@ -16,8 +16,9 @@
 // u * S (bitwise the same numbers as in sweep 1); (3) inside that batch, an ordered inclusive
 // scan over the 16-byte vectors (wave shuffles + LDS offsets) finds the vector, and its owner
 // walks the vector's elements.  All running totals are workgroup-uniform, so every branch on
-// them is uniform.  If rounding keeps the cumulative sum from ever exceeding u * S (u within
-// rounding of 1), the argmax token stays.
+// them is uniform.  If the cumulative sum never exceeds u * S (u within rounding of 1, or a
+// number that is not below 1), the token is the last one with a non-zero probability: that is
+// where the cumulative probability reaches 1.
 #pragma once
 #include "jot_device.h"
 #include "jot_vocab_reduce.h"
@@ -97,7 +98,8 @@ __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
         double S = 0.0;
         for (int base = 0; base < nvec; base += BATCH_VEC) S += batch_total(base);
         for (int v = nvec * VEC; v < V; ++v) S += tail_term(v);
-        const double thresh = (double)uniforms[pos] * S;
+        const float u01 = uniforms[pos];
+        const double thresh = (u01 < 1.0f) ? (double)u01 * S : (double)INFINITY;   // u >= 1: nothing exceeds it
 
         // (2) the batch in which the running total first exceeds thresh
         double running = 0.0;
@@ -112,9 +114,12 @@ __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
         }
 
         if (cross >= 0) {
-            // (3) ordered scan inside the crossing batch, one sub-row of JOT_WG vectors at a time
-            for (int u = 0; u < U; ++u) {
-                const int c = cross + u * JOT_WG + tid;
+            // (3) ordered scan from the start of the crossing batch, one sub-row of JOT_WG vectors at a
+            // time.  The scan sums in another order than the batch totals, so a crossing that lies
+            // within rounding of the batch's end may only show up in the sub-rows after it: keep
+            // going to the end of the row if need be.
+            for (int sub = cross; sub < nvec; sub += JOT_WG) {
+                const int c = sub + tid;
                 float x[VEC];
                 float vs = 0.0f;
                 if (c < nvec) {
@@ -162,7 +167,12 @@ __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
                     break;                                        // uniform: read after the barrier
                 running += sub_total;
             }
-        } else if (nvec * VEC < V) {
+        }
+        // (found_token is latched into a register, with a barrier before anyone writes it again, so
+        // that the branches on it are uniform)
+        bool none = found_token < 0;
+        __syncthreads();
+        if (none && nvec * VEC < V) {
             // crossing not in any whole vector: the few trailing elements, in order
             if (tid == 0) {
                 double cum = running;
@@ -171,6 +181,26 @@ __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
                     if (cum > thresh) { found_token = v; break; }
                 }
             }
+            __syncthreads();
+        }
+        none = found_token < 0;
+        __syncthreads();
+        if (none) {
+            // The cumulative sum never exceeds u * S: u is within rounding of 1 (or not below 1).  The
+            // cumulative probability reaches 1 at the last token with a non-zero probability: take it.
+            int last_nz = -1;
+            for (int c = tid; c < nvec; c += JOT_WG) {
+                float x[VEC];
+                T::unpack(p[c], x);
+#pragma unroll
+                for (int k = 0; k < VEC; ++k)
+                    if (__builtin_amdgcn_exp2f(fmaf(x[k], JOT_LOG2E, shift)) > 0.0f) last_nz = c * VEC + k;
+            }
+            for (int v = nvec * VEC + tid; v < V; v += JOT_WG)
+                if (tail_term(v) > 0.0) last_nz = v;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) last_nz = max(last_nz, __shfl_xor(last_nz, off, 64));
+            if (lane == 0) atomicMax(&found_token, last_nz);
             __syncthreads();
         }
         if (tid == 0) {

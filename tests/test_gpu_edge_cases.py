@@ -359,6 +359,43 @@ def test_sampled_tokens(gpu, dtype, V):
         assert (last["final"] != last["token"]).mean() > 0.3      # sampling really differs from argmax
 
 
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+def test_sampling_at_the_upper_edge_of_the_uniform_range(gpu, dtype):
+    """Uniform numbers at and next to 1 (the input recipe of the other tests keeps them away from
+    there): the largest binary32 number below 1 selects by the ordinary rule; a number the
+    cumulative sum never exceeds (1.0, not a valid draw) selects the last token with a non-zero
+    probability, in the oracle and in the library alike."""
+    import paper_2602_11133_amd as J
+    V, L = 40_000, 6
+    rng = np.random.default_rng(90)
+    lg = rng.standard_normal((1, L, V)).astype(np.float32)
+    lg[0, 0, 777] = 40.0                              # peaked: all but ~1e-13 of the mass on one token
+    lg[0, 1, 777] = 40.0
+    lg[0, 1, 39_000:] = -np.inf                       # zero-probability tail
+    lg[0, 2, 30_001:] = -np.inf
+    lg[0, 3, :] = 0.0                                 # flat
+    lg[0, 3, V - 3:] = -np.inf
+    lg[0, 4, V - 1] = 40.0                            # peaked on the last token
+    lg[0, 5, 0] = 40.0                                # peaked on the first token
+    if dtype == O.BF16:
+        lg = bf16_bits_to_f32(f32_to_bf16_bits(lg)).reshape(lg.shape)
+    below_one = np.nextafter(np.float32(1.0), np.float32(0.0))
+    u = np.array([[below_one, 1.0, 1.0, 1.0, below_one, 1.0]], np.float32)
+    p = O.OracleParams(B=1, L=L, V=V, dtype=dtype, conf_mode=O.CONF_MAXPROB, tau_max=0.0, tau_min=0.0, D=0)
+    st = O.OracleState.init(p, np.zeros((1, L), np.int32), np.ones((1, L), bool))
+    rec = st.step(as_rows(lg.reshape(L, V), dtype), sample_u=u)
+    assert rec.commit.all()
+    assert rec.final_token.tolist()[:3] == [777, 38_999, 30_000] and rec.final_token[3] == V - 4
+    assert rec.final_token[4] == V - 1
+    jp = J.JotParams(B=1, L=L, V=V, dtype=dtype, conf_mode=O.CONF_MAXPROB, tau_max=0.0, tau_min=0.0, gamma=0.5,
+                     D=0, eps=1e-12, gen_start=0, block_size=0)
+    g = gpu.GpuJot(jp, np.zeros((1, L), np.int32), np.ones((1, L), bool))
+    g.step(to_device(lg, dtype, V), stride_b=L * V, stride_l=V, uniforms=u)
+    np.testing.assert_array_equal(g.last()["final"], rec.final_token)
+    np.testing.assert_array_equal(g.tokens(), st.tokens)
+    g.close()
+
+
 def test_sampling_leaves_unfinalized_positions_alone(gpu):
     p, tokens, masked, seq = random_case(51, B=2, L=60, V=500, gs=8, conf_mode=O.CONF_RATIO, tau_max=50.0,
                                          tau_min=1.0, gamma=0.5, D=8, steps=5)
@@ -368,6 +405,40 @@ def test_sampling_leaves_unfinalized_positions_alone(gpu):
 
 
 # --------------------------------------------------------------------------- sizes, streams, run-time errors
+
+def test_active_count_can_be_polled_without_waiting(gpu):
+    """jot_active_count_poll never blocks: it returns the count of the last COMPLETED step and how
+    many steps have completed; polled until the enqueued step shows up it agrees with the waiting
+    call, and it is consistent (never a count of one step labelled with another)."""
+    import time
+    import paper_2602_11133_amd as J
+    p, tokens, masked, seq = random_case(77, B=3, L=90, V=4000, gs=10, conf_mode=O.CONF_RATIO, tau_max=40.0,
+                                         tau_min=1.0, gamma=0.5, D=8, steps=4)
+    jp = J.JotParams(B=p.B, L=p.L, V=p.V, dtype=p.dtype, conf_mode=p.conf_mode, tau_max=p.tau_max, tau_min=p.tau_min,
+                     gamma=p.gamma, D=p.D, eps=p.eps, gen_start=p.gen_start, block_size=p.block_size)
+    st = O.OracleState.init(p, tokens, masked)
+    g = gpu.GpuJot(jp, tokens, masked)
+    n0, done0 = J.jot_active_count_poll(g.h)
+    assert (n0, done0) == (st.active_count(), 0)
+    for n, logits in enumerate(seq, 1):
+        lg = np.array(logits, np.float32)
+        clear_guard_band(st, lg)
+        st.step(as_rows(lg.reshape(p.B * p.L, p.V)[st.active_list()], p.dtype))
+        sl = p.V + (-p.V) % 4
+        g.step(to_device(lg, p.dtype, sl), stride_b=p.L * sl, stride_l=sl)
+        deadline = time.time() + 20.0
+        seen = set()
+        while True:
+            cnt, done = J.jot_active_count_poll(g.h)
+            seen.add((cnt, done))
+            if done == n or time.time() > deadline:
+                break
+        assert done == n and cnt == st.active_count()
+        assert seen <= {(n0, n - 1), (cnt, n)}               # only the old or the new snapshot, never a mix
+        n0 = cnt
+        assert J.jot_active_count(g.h) == cnt and J.jot_step_index(g.h) == n
+    g.close()
+
 
 def test_very_long_vocabulary_single_rows(gpu):
     # one row of 3 000 001 logits (12 MB): many pieces per row, 64-bit-safe index arithmetic, ragged end

@@ -363,10 +363,14 @@ def test_step_replayed_from_a_captured_graph(gpu, cid, scheduled):
         act_full, rec = oracle_and_fill(n)
         torch.cuda.synchronize()
         graph.replay()
-        torch.cuda.synchronize()
+        if n % 2:
+            torch.cuda.synchronize()
+        else:       # tell the library where the replay runs: its read-backs then wait for that stream only
+            J.jot_wait_on_stream(g.h, torch.cuda.current_stream().cuda_stream)
         replays += 1
         gpu.compare_step(g.last(), rec, act_full, TOL[cfg.dtype])
         assert g.active_count() == run.state.active_count()
+        assert J.jot_step_index(g.h) == n                      # counted on the device, replays included
     assert replays >= 3
     np.testing.assert_array_equal(g.tokens(), run.state.tokens)
     np.testing.assert_array_equal(g.masked(), run.state.masked)

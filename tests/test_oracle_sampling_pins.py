@@ -81,3 +81,26 @@ def test_peaked_distribution_samples_its_argmax():
     row[17] = 0.0
     for u in (1e-9, 0.3, 0.999999):      # (u = 0 would pick token 0, whose mass e^-40 is tiny but not zero)
         assert O.sample_row(row, O.F32, u)[0] == 17
+
+
+def test_convention_at_the_upper_edge():
+    # Inverse-CDF sampling takes the first token whose cumulative probability exceeds u; the
+    # cumulative probability reaches 1 at the last token with a non-zero probability, so a number
+    # that the rounded sum never exceeds (u = 1, not a valid draw from [0, 1)) selects that token,
+    # and the largest binary32 number below 1 selects by the ordinary rule.
+    V = 64
+    row = np.full(V, -2.0, np.float32)
+    row[7] = 30.0                      # p = 1 - 63 e^-32 ~ 1 - 8e-13
+    row[50:] = -np.inf                 # zero-probability tail
+    below_one = float(np.nextafter(np.float32(1.0), np.float32(0.0)))
+    assert O.sample_row(row, O.F32, below_one)[0] == 7
+    assert O.sample_row(row, O.F32, 1.0)[0] == 49
+    assert O.sample_row(row, O.F32, 0.0)[0] == 0
+    flat = np.zeros(V, np.float32)
+    flat[40:] = -np.inf
+    assert O.sample_row(flat, O.F32, below_one)[0] == 39 and O.sample_row(flat, O.F32, 1.0)[0] == 39
+    # brute force on the explicit probability vector
+    pi = O.softmax_row(row, O.F32)
+    cum = np.cumsum(pi)
+    assert int(np.argmax(cum > below_one)) == 7 and not (cum > 1.0).any()
+    assert np.flatnonzero(pi > 0)[-1] == 49
