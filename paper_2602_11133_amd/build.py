@@ -8,7 +8,7 @@ LIB = os.path.join(_HERE, "_lib", "libjot.so")
 PROBE_LIB = os.path.join(_HERE, "_lib", "libjot_probe.so")
 PROBE_SRC = os.path.join(CSRC, "jot_probe.hip")
 SOURCES = ["jot_api.hip"]
-HEADERS = ["jot_device.h", "jot_vocab_reduce.h", "jot_decide.h", "jot_compact.h", "jot_schedule.h", "jot_sample.h", "jot_row_step.h", "jot_stability.h", "jot_vocab_reduce_kl.h",
+HEADERS = ["jot_device.h", "jot_vocab_reduce.h", "jot_decide.h", "jot_compact.h", "jot_schedule.h", "jot_sample.h", "jot_row_step.h",
            os.path.join("..", "..", "include", "jot.h")]
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

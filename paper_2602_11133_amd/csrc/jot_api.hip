@@ -4,6 +4,7 @@
 #include "../../include/jot.h"
 
 #include <hip/hip_runtime.h>
+#include <chrono>
 #include <math.h>
 #include <mutex>
 #include <new>
@@ -16,7 +17,6 @@
 #include "jot_sample.h"
 #include "jot_schedule.h"
 #include "jot_vocab_reduce.h"
-#include "jot_vocab_reduce_kl.h"
 
 // Working memory of jot_step_static() (see below): one fixed array per GPU.
 static __device__ __align__(256) unsigned char scratch[JOT_STATIC_MAX_WORKSPACE];
@@ -38,6 +38,7 @@ constexpr int kFallbackCus = 256;
 #define JOT_ITEMS_PER_WG 1
 #endif
 constexpr int kItemsPerWg = JOT_ITEMS_PER_WG;
+constexpr int kPollMicroseconds = 300;   // how long a wait polls the pinned step counter before it blocks on the event
 constexpr int kPerRowStepMax = 2048;   // longest per-row examined list handled by the one-launch row kernel
 
 struct Layout {
@@ -133,6 +134,7 @@ struct jot_state {
     hipEvent_t done;
     bool have_done;
     bool per_row_step;          // decision + schedule + row counts in one per-row launch
+    bool host_counts_steps;     // every step so far was enqueued eagerly: s->step is what the device will count to
     bool host_resources;        // owns pinned host counters and events (false: a transient state on the caller's stack)
     bool profile;
     hipEvent_t prof0[JOT_PROFILE_RING], prof1[JOT_PROFILE_RING];
@@ -193,6 +195,7 @@ int enqueue_compaction(jot_state* s, bool creating, hipStream_t st, bool count_r
         // transient state: nothing on the host waits for it
     } else if (stream_is_capturing(st)) {
         s->sync_device = true;
+        s->host_counts_steps = false;       // a captured step runs when (and as often as) its graph is replayed
     } else {
         if (hipEventRecord(s->done, st) != hipSuccess) return JOT_ERR_HIP;
         s->have_done = true;
@@ -201,15 +204,36 @@ int enqueue_compaction(jot_state* s, bool creating, hipStream_t st, bool count_r
     return JOT_OK;
 }
 
+// Waits until the results of every step enqueued so far can be read.  The last kernel of a step
+// stores its step number into pinned host memory after everything else it writes, so short steps
+// are awaited by polling that number for a bounded time (a few microseconds of latency instead of
+// an event wait); long steps, and states whose steps are replayed from a graph (the host cannot
+// count those), fall back to the event / the device.
 int wait_done(jot_state* s)
 {
     if (!s) return JOT_ERR_NULL_POINTER;
     if (s->sync_device) {
         if (hipDeviceSynchronize() != hipSuccess) return JOT_ERR_HIP;
-    } else if (s->have_done && hipEventSynchronize(s->done) != hipSuccess) {
-        return JOT_ERR_HIP;
+        return JOT_OK;
     }
-    return JOT_OK;
+    if (!s->have_done) return JOT_OK;
+    if (s->host_counts_steps) {
+        const volatile int32_t* done = &s->host->steps_done;
+        const auto t0 = std::chrono::steady_clock::now();
+        for (int spins = 0; *done < s->step; ++spins) {
+            if ((spins & 63) == 63 &&
+                std::chrono::steady_clock::now() - t0 > std::chrono::microseconds(kPollMicroseconds))
+                break;
+#if defined(__x86_64__)
+            __builtin_ia32_pause();
+#endif
+        }
+        if (*done >= s->step) {
+            __atomic_thread_fence(__ATOMIC_ACQUIRE);
+            return JOT_OK;
+        }
+    }
+    return hipEventSynchronize(s->done) == hipSuccess ? JOT_OK : JOT_ERR_HIP;
 }
 
 // Working memory of jot_step_static(): one fixed array per GPU, held until the process ends.
@@ -287,8 +311,8 @@ DeviceShape shape_of(int dev)
         d.occ[JOT_F32] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotF32>), JotF32::WG);
         d.occ[JOT_BF16] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotBF16>), JotBF16::WG);
         // the reduction with the stability term has its own register footprint, hence its own grid
-        d.occ_kl[JOT_F32] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kl_kernel<JotF32KL>), JotF32KL::WG);
-        d.occ_kl[JOT_BF16] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kl_kernel<JotBF16KL>), JotBF16KL::WG);
+        d.occ_kl[JOT_F32] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotF32KL>), JotF32KL::WG);
+        d.occ_kl[JOT_BF16] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotBF16KL>), JotBF16KL::WG);
         d.known = true;
     }
     return d;
@@ -323,6 +347,7 @@ void configure(jot_state* s, const jot_params* p, int dev, char* ws)
     }
     s->have_done = false;
     s->profile = false;
+    s->host_counts_steps = true;
     s->host_resources = false;
     s->host = nullptr;
     s->host_dev = s->at<HostCounters>(s->lay.host_block);     // replaced by pinned host memory if the state owns some
@@ -424,20 +449,20 @@ int enqueue_step(jot_state* s, const void* logits_dev, int64_t stride_b, int64_t
         if (hipEventRecord(s->prof0[slot], st) != hipSuccess) return JOT_ERR_HIP;
     }
     if (do_kl && p.dtype == JOT_F32)
-        hipLaunchKernelGGL(jot_vocab_reduce_kl_kernel<JotF32KL>, dim3(s->grid_reduce_kl), dim3(JotF32KL::WG), 0, st,
+        hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotF32KL>, dim3(s->grid_reduce_kl), dim3(JotF32KL::WG), 0, st,
                            logits_dev, opt->prev_logits_dev, stride_b, stride_l, p.L, p.V, s->frame,
                            s->at<JotPartial>(s->lay.partials), s->target_items_kl, INFINITY);
     else if (do_kl)
-        hipLaunchKernelGGL(jot_vocab_reduce_kl_kernel<JotBF16KL>, dim3(s->grid_reduce_kl), dim3(JotBF16KL::WG), 0, st,
+        hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotBF16KL>, dim3(s->grid_reduce_kl), dim3(JotBF16KL::WG), 0, st,
                            logits_dev, opt->prev_logits_dev, stride_b, stride_l, p.L, p.V, s->frame,
                            s->at<JotPartial>(s->lay.partials), s->target_items_kl, INFINITY);
     else if (p.dtype == JOT_F32)
         hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotF32>, dim3(s->grid_reduce), dim3(JotF32::WG), 0, st,
-                           logits_dev, stride_b, stride_l, reduce_L, p.V, reduce_frame,
+                           logits_dev, nullptr, stride_b, stride_l, reduce_L, p.V, reduce_frame,
                            s->at<JotPartial>(s->lay.partials), s->target_items, INFINITY);
     else
         hipLaunchKernelGGL(jot_vocab_reduce_kernel<JotBF16>, dim3(s->grid_reduce), dim3(JotBF16::WG), 0, st,
-                           logits_dev, stride_b, stride_l, reduce_L, p.V, reduce_frame,
+                           logits_dev, nullptr, stride_b, stride_l, reduce_L, p.V, reduce_frame,
                            s->at<JotPartial>(s->lay.partials), s->target_items, INFINITY);
     if (hipGetLastError() != hipSuccess) return JOT_ERR_HIP;
     if (s->profile && !capturing) {

@@ -7,7 +7,6 @@
 // kernels afterwards, so every thread of this kernel sees the mask as it was when the step began.
 #pragma once
 #include "jot_device.h"
-#include "jot_stability.h"
 
 // Arrays the decision writes or reads, all in the caller's workspace.
 struct JotDecideIO {
@@ -52,21 +51,17 @@ struct JotDecideParams {
 __device__ __forceinline__ void jot_decide_one(const JotDecideParams& prm, const JotDecideIO& io,
                                                int32_t step, int64_t r, int pieces)
 {
-    // ---- merge the pieces of the row, in piece order
-    const JotPartial* q = io.partials + r * pieces;
-    float m1 = q[0].m1, m2 = q[0].m2, M = q[0].M, s = q[0].s, cross = q[0].pad[0];
-    int32_t idx = q[0].idx;
-    for (int j = 1; j < pieces; ++j)
-        jot_merge_kl(m1, idx, m2, M, s, cross, q[j].m1, q[j].idx, q[j].m2, q[j].M, q[j].s, q[j].pad[0]);
+    // ---- merge the pieces of the row, in piece order: S_raw = sum_v exp(l_v - m1), cross on the same scale
+    float m1, m2, S_raw, cross;
+    int32_t idx;
+    jot_merge_pieces(io.partials + r * pieces, pieces, m1, idx, m2, S_raw, cross);
 
     if (m1 == -INFINITY)
         idx = 0;            // every logit is -inf: all are equal, the smallest index is 0
 
-    // ---- probabilities: S = sum_v exp(l_v - m1) = s * 2^(M - m1*log2 e); p1 = 1/S, p2 = e^(m2-m1)/S
-    const float S_raw = s * exp2f(fmaf(-m1, JOT_LOG2E, M));
+    // ---- probabilities: p1 = 1/S, p2 = e^(m2-m1)/S
     const float S = fmaxf(S_raw, 1.0f);     // the maximum itself contributes exp(0) = 1: rounding may not go below
-    const bool has_softmax = (S_raw >= 0.5f) && (S_raw < INFINITY) &&           // false for NaN
-                             (m1 >= -JOT_LOGIT_LIMIT) && (m1 <= JOT_LOGIT_LIMIT);
+    const bool has_softmax = (S_raw >= 0.5f) && (S_raw < INFINITY);            // false for NaN
     const float p1 = 1.0f / S;
     const float p2 = expf(m2 - m1) / S;
     float conf;
@@ -104,13 +99,13 @@ __device__ __forceinline__ void jot_decide_one(const JotDecideParams& prm, const
     const bool exit_now = has_softmax && (conf >= tau);         // Eq. 6
 
     // ---- KL stability rule: needs the log-normalizer this position had in the step just before.
-    // D(pi || pi') = A/S - (m1 + ln S) + (m1' + ln S'); A and s share their scaling, so A/S = cross/s.
+    // D(pi || pi') = A/S - (m1 + ln S) + (m1' + ln S'); A (= cross) and S_raw share their scaling.
     const double nan64 = __longlong_as_double(0x7ff8000000000000ll);
     const double lse = has_softmax ? (double)m1 + log((double)S) : nan64;
     bool stable = false;
     float kl_out = __uint_as_float(0x7fc00000u);
     if (prm.do_kl && has_softmax && io.lse_step[pos] == step - 1) {
-        const double kl = (double)cross / (double)s - lse + io.lse[pos];
+        const double kl = (double)cross / (double)S_raw - lse + io.lse[pos];
         kl_out = (float)kl;
         stable = (kl <= (double)prm.kl_threshold) && (p1 >= prm.kl_min_prob);
     }

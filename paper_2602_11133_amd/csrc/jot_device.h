@@ -12,13 +12,17 @@
 // Partial result of the vocabulary reduction over a contiguous piece of one logit row.
 // The exponentials are accumulated in base 2 against an integer-valued reference M:
 //   s = sum_v 2^(l_v * log2(e) - M),  so that  sum_v exp(l_v - m1) = s * 2^(M - m1 * log2(e)).
+// A piece whose maximum lies outside the range in which that base-2 form is accurate is summed
+// a second time directly against its own maximum (`direct` != 0):  s = sum_v exp(l_v - m1).
 struct __align__(32) JotPartial {
     float m1;       // largest logit of the piece (-inf if the piece is empty)
     int32_t idx;    // its vocabulary index, smallest index among equal maxima
     float m2;       // second largest logit of the piece as a multiset
     float M;        // reference exponent (integer valued, -inf if nothing finite was seen)
     float s;        // scaled sum of exponentials
-    float pad[3];
+    float cross;    // KL variant: sum_v (weight of v, scaled like s) * (l_v - l'_v); else 0
+    float direct;   // != 0: s and cross are relative to m1 itself, M is unused
+    float pad;
 };
 
 struct JotSplit {
@@ -90,11 +94,12 @@ struct JotHostBlock {
 
 #define JOT_LOG2E 1.44269504088896340736f
 
-// Supported range of a row's LARGEST logit.  The exponent sums work in base 2 on l * log2(e);
-// that product is exact to better than one unit only while it stays below 2^23, i.e. for
-// |l| < 5.8e6.  A row whose maximum lies outside +-JOT_LOGIT_LIMIT is reported as having no
-// softmax (never finalized, counted as an anomaly).  Entries far BELOW the range (fill values
-// such as -1e9, -1e30, -FLT_MAX, -inf used to mask tokens) are fine: they contribute 0.
+// Range of a piece's LARGEST logit within which the one-pass base-2 sums are used.  They work on
+// l * log2(e); that product is exact to better than one unit only while it stays below 2^23, i.e.
+// for |l| < 5.8e6.  A piece whose maximum lies outside +-JOT_LOGIT_LIMIT (no model produces such
+// logits, but every finite row has a softmax) is summed a second time, directly against its
+// maximum.  Entries far BELOW the range (fill values such as -1e9, -1e30, -FLT_MAX, -inf used to
+// mask tokens) are fine in the one-pass form: they contribute 0.
 #define JOT_LOGIT_LIMIT 4.0e6f
 #define JOT_EXPONENT_FLOOR (-8388608.0f)   // -2^23: lowest reference exponent a lane will take
 
@@ -114,4 +119,43 @@ __device__ __forceinline__ void jot_merge(float& m1, int32_t& idx, float& m2, fl
     const float fb = (bM == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(bM - newM);
     s = s * fa + bs * fb;
     M = newM;
+}
+
+// Sum of exponentials of a piece relative to the piece's own maximum, sum_v exp(l_v - m1), and the
+// factor that brings the piece's scaled sums (s, cross) to that form.
+__device__ __forceinline__ float jot_piece_scale(const JotPartial& q)
+{
+    if (q.direct != 0.0f) return 1.0f;
+    if (q.m1 == -INFINITY) return 0.0f;             // nothing but -inf in the piece: it adds nothing (a NaN sum stays NaN)
+    return exp2f(fmaf(-q.m1, JOT_LOG2E, q.M));      // 2^(M - m1 log2 e)
+}
+
+// Merge of the pieces of one row in piece order, in the form the decision needs: the row's
+// (m1, idx, m2), S = sum_v exp(l_v - m1) and the cross term on the same scale.  Larger logit
+// first, then smaller index; m2 is the second entry of the merged multiset.
+__device__ __forceinline__ void jot_merge_pieces(const JotPartial* q, int pieces, float& m1, int32_t& idx, float& m2,
+                                                 float& S, float& cross)
+{
+    m1 = q[0].m1; idx = q[0].idx; m2 = q[0].m2;
+    {
+        const float f = jot_piece_scale(q[0]);
+        S = q[0].s * f;
+        cross = q[0].cross * f;
+    }
+    for (int j = 1; j < pieces; ++j) {
+        const float f = jot_piece_scale(q[j]);
+        const float Sj = q[j].s * f, Cj = q[j].cross * f;
+        const float bm1 = q[j].m1;
+        const bool a_wins = (m1 > bm1) || (m1 == bm1 && idx < q[j].idx);
+        const float loser = a_wins ? bm1 : m1;
+        m2 = fmaxf(fmaxf(m2, q[j].m2), loser);
+        idx = a_wins ? idx : q[j].idx;
+        const float top = a_wins ? m1 : bm1;
+        // exp(-inf - top) = 0 for an empty piece; equal maxima give factors of exactly 1
+        const float fa = (m1 == top) ? 1.0f : expf(m1 - top);
+        const float fb = (bm1 == top) ? 1.0f : expf(bm1 - top);
+        S = S * fa + Sj * fb;
+        cross = cross * fa + Cj * fb;
+        m1 = top;
+    }
 }

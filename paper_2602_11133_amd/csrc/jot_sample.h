@@ -67,7 +67,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
         const int64_t row_off = compact ? (int64_t)r * stride_l : (int64_t)b * stride_b + (int64_t)i * stride_l;
         const char* row = reinterpret_cast<const char*>(logits) + row_off * T::ESZ;
         const jot_u32x4* __restrict__ p = reinterpret_cast<const jot_u32x4*>(row);
-        const float shift = -last_m1[r] * JOT_LOG2E;             // exp(l - m1) = 2^(l*log2e + shift)
+        const float top = last_m1[r];                             // exp(l - m1) = 2^((l - m1) log2 e), any magnitude
         const int nvec = V / VEC;
         if (tid == 0) found_token = -1;
         __syncthreads();
@@ -84,14 +84,14 @@ __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
                     float vs = 0.0f;
 #pragma unroll
                     for (int k = 0; k < VEC; ++k)
-                        vs += __builtin_amdgcn_exp2f(fmaf(x[k], JOT_LOG2E, shift));
+                        vs += __builtin_amdgcn_exp2f((x[k] - top) * JOT_LOG2E);
                     part += (double)vs;
                 }
             }
             return jot_wg_total(part, lds);
         };
         auto tail_term = [&](int v) -> double {
-            return (double)__builtin_amdgcn_exp2f(fmaf(T::scalar(row, v), JOT_LOG2E, shift));
+            return (double)__builtin_amdgcn_exp2f((T::scalar(row, v) - top) * JOT_LOG2E);
         };
 
         // (1) total
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
                     T::unpack(p[c], x);
 #pragma unroll
                     for (int k = 0; k < VEC; ++k) {
-                        x[k] = __builtin_amdgcn_exp2f(fmaf(x[k], JOT_LOG2E, shift));
+                        x[k] = __builtin_amdgcn_exp2f((x[k] - top) * JOT_LOG2E);
                         vs += x[k];
                     }
                 } else {
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
                 T::unpack(p[c], x);
 #pragma unroll
                 for (int k = 0; k < VEC; ++k)
-                    if (__builtin_amdgcn_exp2f(fmaf(x[k], JOT_LOG2E, shift)) > 0.0f) last_nz = c * VEC + k;
+                    if (__builtin_amdgcn_exp2f((x[k] - top) * JOT_LOG2E) > 0.0f) last_nz = c * VEC + k;
             }
             for (int v = nvec * VEC + tid; v < V; v += JOT_WG)
                 if (tail_term(v) > 0.0) last_nz = v;

@@ -569,28 +569,52 @@ def test_fill_values_of_any_size(gpu, dtype):
     assert toks[0, 4] == 5 and toks[0, 0] < 30_000 and toks[0, 1] >= 60_000 and toks[0, 5] == 0
 
 
-@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
-def test_rows_beyond_the_library_range_are_left_masked(gpu, dtype):
-    """A stated limitation of the LIBRARY, not of the method (the oracle evaluates these rows and
-    is deliberately not consulted): a row whose largest logit lies outside [-4e6, 4e6] is reported
-    as having no softmax -- left masked and counted -- while its argmax is still reported."""
-    import paper_2602_11133_amd as J
-    V, L = 70_000, 4
-    rng = np.random.default_rng(71)
+def far_rows(rng, V, L):
+    """Rows whose entries lie far from zero (beyond +-4e6, where the reduction's one-pass base-2
+    sums stop being accurate and it sums the row a second time against its maximum): Section 4.1
+    defines their softmax like any other, from the differences to the row maximum."""
     lg = rng.standard_normal((1, L, V)).astype(np.float32)
-    lg[0, 0, :] = 1.0e30
-    lg[0, 1, 123] = 5.0e6
-    lg[0, 2, :] = -1.0e9
-    jp = J.JotParams(B=1, L=L, V=V, dtype=dtype, conf_mode=O.CONF_MAXPROB, tau_max=0.0, tau_min=0.0, gamma=0.5,
-                     D=0, eps=1e-12, gen_start=0, block_size=0)
-    g = gpu.GpuJot(jp, np.zeros((1, L), np.int32), np.ones((1, L), bool))
-    dev = to_device(lg, dtype, V)
-    g.step(dev, stride_b=L * V, stride_l=V)
-    assert g.masked()[0].tolist() == [True, True, True, False]
-    assert J.jot_anomaly_count(g.h) == 3
-    last = g.last()
-    assert last["token"][:3].tolist() == [0, 123, 0] and np.isnan(last["conf"][:3]).all()
-    g.close()
+    lg[0, 0, :] = 1.0e30                                  # constant, huge: uniform distribution
+    lg[0, 1, 123] = 5.0e6                                 # one huge outlier: p1 = 1
+    lg[0, 2, :] = -1.0e9                                  # constant, very negative: uniform
+    lg[0, 3, :] = (-5.0e6 - 0.5 * (np.arange(V) % 11)).astype(np.float32)    # structure 5e6 below zero
+    lg[0, 4, :] = (2.0 ** 24 + 2.0 * (np.arange(V) % 7)).astype(np.float32)  # ... and 1.7e7 above
+    lg[0, 5, :] = -3.0e38
+    lg[0, 5, V // 2] = -6.0e6                             # fill values around one very negative real logit
+    lg[0, 6, :] = np.where(np.arange(V) % 2 == 0, 4.5e6, -4.5e6)            # both ends of the range
+    lg[0, 7, V - 1] = 1.0e10                              # the outlier sits in the ragged tail
+    return lg
+
+
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+@pytest.mark.parametrize("V", [70_000, 300_007])          # whole rows / rows cut into pieces
+def test_rows_far_from_zero(gpu, dtype, V):
+    L = 8
+    rng = np.random.default_rng(71)
+    p = O.OracleParams(B=1, L=L, V=V, dtype=dtype, conf_mode=O.CONF_MAXPROB, tau_max=0.9, tau_min=0.9, D=0)
+    lg = far_rows(rng, V, L)
+    u = rng.random((1, L), dtype=np.float32)
+    toks, msk, log, last = check_case(gpu, p, np.zeros((1, L), np.int32), np.ones((1, L), bool), [lg], clear=False,
+                                      uniforms=[u])
+    assert msk[0].tolist() == [True, False, True, True, True, False, True, False]
+    assert toks[0, 1] == 123 and toks[0, 5] == V // 2 and toks[0, 7] == V - 1
+    assert last["token"].tolist()[:4] == [0, 123, 0, 0] and last["token"][4] == (6 if dtype == O.F32 else 0)
+
+
+@pytest.mark.parametrize("dtype", [O.F32, O.BF16])
+def test_stability_rule_on_rows_far_from_zero(gpu, dtype):
+    # the cross term of the divergence rides along with the second summation of such rows
+    V, L = 70_000, 8
+    rng = np.random.default_rng(72)
+    p = O.OracleParams(B=1, L=L, V=V, dtype=dtype, conf_mode=O.CONF_MAXPROB, tau_max=2.0, tau_min=2.0, D=0)
+    a = far_rows(rng, V, L)
+    b = a.copy()
+    b[0, 3, ::5] -= 1.0                                   # moved (in steps binary32 resolves at 5e6)
+    b[0, 4, ::3] += 4.0
+    b[0, 6, 1::2] = -4.6e6                                # moved where the weight is 0: no change
+    toks, msk, log, last = check_case(gpu, p, np.zeros((1, L), np.int32), np.ones((1, L), bool), [a, b, b],
+                                      clear=False, kl=[(0.05, 0.0)] * 3)
+    assert np.isfinite(last["kl"]).all() and len(log) > 0
 
 
 # --------------------------------------------------------------------------- row-wide early commit
