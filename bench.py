@@ -35,24 +35,26 @@ FLUSH_BYTES = 1 << 30
 # HBM traffic of the vocabulary reduction from rocprofv3 counters, as a ratio to the algorithmic
 # bytes (examined positions x V x element size) of the same launches: (FETCH_SIZE x 2.000 +
 # WRITE_SIZE x 1.000) KiB, factors from a plain 1 GiB copy kernel in the same runs; see
-# profiles/vocab_reduce_cfg5_hbm_traffic.md.  Valid for the kernel sources with these hashes and
-# for this workload and logit type; otherwise bench.py reports null.
+# profiles/vocab_reduce_cfg5_hbm_traffic.md and profiles/vocab_reduce_bf16_hbm_traffic.md.  Valid
+# for the kernel sources with these hashes and for these workloads and logit types; otherwise
+# bench.py reports null.
 MEASURED_TRAFFIC = {
-    "config": 5, "dtype": "f32", "hbm_bytes_per_algorithmic_byte": 1.00061,
-    "sha256": {"jot_vocab_reduce.h": "743d69b2ad15a65d2f3c50f6d353f88fb4707f10e68ad592f94b39157fc0d610",
-               "jot_device.h": "74734f6e5886fe8dc148ec3382d591ffcd23b828392147475546fbe12b8c44d9"},
+    "hbm_bytes_per_algorithmic_byte": {(5, "f32"): 1.00059, (5, "bf16"): 1.00104, (3, "bf16"): 1.00099},
+    "sha256": {"jot_vocab_reduce.h": "c788435bdfb4efa57bb38ce678505b3b45f560cc3790d853c336cb5fe39a0e6b",
+               "jot_device.h": "4bc5345d3b6a5f57b7b1c08f484939f2ee3b848d84e19456f481d56f6fb5ed15"},
 }
 
 
 def measured_traffic_ratio(config: int, dtype: str):
-    if config != MEASURED_TRAFFIC["config"] or dtype != MEASURED_TRAFFIC["dtype"]:
+    ratio = MEASURED_TRAFFIC["hbm_bytes_per_algorithmic_byte"].get((config, dtype))
+    if ratio is None:
         return None
     for name, want in MEASURED_TRAFFIC["sha256"].items():
         path = os.path.join(ROOT, "paper_2602_11133_amd", "csrc", name)
         with open(path, "rb") as f:
             if hashlib.sha256(f.read()).hexdigest() != want:
                 return None
-    return float(MEASURED_TRAFFIC["hbm_bytes_per_algorithmic_byte"])
+    return float(ratio)
 
 
 def host_threads() -> int:
@@ -344,7 +346,7 @@ def main():
         kms = [seconds / K * 1e3] * K
     k_sec = sum(kms) * 1e-3 / K                     # average launch duration
     achieved = k_bytes / k_sec / 1e9
-    plain = args.dtype is None and args.schedule == "none" and not args.sample and not args.graph and args.kl is None
+    plain = args.schedule == "none" and not args.sample and not args.graph and args.kl is None
     ratio = measured_traffic_ratio(args.config, dtype_name) if plain else None
 
     def rate_record(n_examined, sec, kernel_ms):
