@@ -133,10 +133,10 @@ def test_flip_budget_arithmetic_printed(printed):
 
 
 def test_committed_positions_leave_the_runner_up_a_small_head_to_head_share():
-    # Section 5 (proof sketch of the flip bound): at commit time the runner-up holds at most a
-    # 1/(1 + tau) share of the head-to-head probability against the leader -- with the
-    # position's own threshold tau^i under spatial modulation.  Checked on every position a
-    # multi-step decode commits, from the full probability vectors.
+    # Fact used by Section 5's flip bound: a position only commits when r = p1/p2 >= tau, so among
+    # the two leading tokens alone the second one then has probability p2/(p1 + p2) <= 1/(1 + tau)
+    # (here tau is the position's own tau^i, since the threshold is spatially modulated).  Checked
+    # from the full probability vectors on every position a multi-step decode commits.
     rng = np.random.default_rng(11)
     B, L, V, gs = 2, 40, 30, 6
     p = O.OracleParams(B=B, L=L, V=V, conf_mode=O.CONF_RATIO, tau_max=20.0, tau_min=1.5, gamma=0.5, D=4, gen_start=gs)
