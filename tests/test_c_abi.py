@@ -82,6 +82,37 @@ def test_null_state_is_an_error_not_a_crash():
     assert J.jot_strerror(0) == "success"
 
 
+def test_static_entry_point_rejects_bad_arguments_before_any_device_work():
+    p = good()
+    sb, sl = p.L * p.V, p.V
+
+    def call(pp=p, logits=4096, stride_b=sb, stride_l=sl, tok=4096, msk=4096, act=4096, cnt=4096):
+        return J.load_library().jot_step_static(ctypes.byref(pp) if pp is not None else None, logits, stride_b,
+                                                stride_l, tok, msk, act, cnt, None)
+
+    assert call(pp=None) == -2
+    assert call(tok=None) == -2 and call(msk=None) == -2 and call(act=None) == -2 and call(cnt=None) == -2
+    assert call(logits=None) == -2
+    assert call(tok=4098) == -5 and call(act=4098) == -5 and call(cnt=4100) == -5 and call(logits=4104) == -5
+    assert call(stride_l=p.V - 1) == -1 and call(stride_b=1) == -1
+    bad = good()
+    bad.V = 1
+    assert call(pp=bad) == -1
+    big = good()
+    big.B, big.L = 64, 1280
+    assert J.jot_workspace_bytes(big) > J.JOT_STATIC_MAX_WORKSPACE
+    assert call(pp=big, stride_b=big.L * big.V) == -10
+    assert "scratch" in J.jot_strerror(-10)
+
+
+def test_poll_and_wait_calls_reject_a_null_state():
+    lib = J.load_library()
+    assert lib.jot_active_count_poll(None, None) == -2
+    assert lib.jot_wait_on_stream(None, None) == -2
+    assert lib.jot_step_index(None) == -2
+    assert lib.jot_anomaly_count(None) == -2
+
+
 def test_package_has_no_cpu_fallback():
     # the binding computes nothing: it must not import the oracle or numpy math paths for the method
     src = open(os.path.join(ROOT, "paper_2602_11133_amd", "binding.py")).read()
