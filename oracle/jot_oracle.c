@@ -119,9 +119,11 @@ int jot_oracle_softmax_row(const void *row, int dtype, int32_t V, double *pi)
  * Sampling-based finalization (Section 4.1, "Early-Exit Decision": the finalized token may be
  * sampled from pi instead of taking the argmax).  Inverse-CDF sampling with a uniform number u
  * in [0, 1) supplied by the caller: the token is the first index v whose cumulative probability
- * pi_0 + ... + pi_v exceeds u.  The cumulative probability reaches 1 at the last index with a
- * non-zero probability: that index is returned for u >= 1 (not a valid draw, but defined), and
- * also if rounding leaves the total just below u.  Also reports the cumulative probability just below and
+ * pi_0 + ... + pi_v exceeds u.  Section 4.1 only says that the token may be sampled from pi; the
+ * reading taken for the upper edge: the cumulative probability reaches 1 at the last index with a
+ * non-zero probability, so that index is returned for u >= 1 (not a valid draw from [0, 1), but
+ * defined -- in double the rounded running sum may or may not exceed 1.0, which must not decide),
+ * and also if rounding leaves the total just below u.  Also reports the cumulative probability just below and
  * just above the chosen token (so a test can tell how far u is from either edge).
  * Returns -1 for a row without a softmax.
  */
