@@ -391,7 +391,7 @@ def main():
         "step1": step1,
         "whole_loop": whole,
         "roofline": {"bound": "hbm",
-                     "kernel": "jot_vocab_reduce_kl_kernel" if args.kl is not None else "jot_vocab_reduce_kernel",
+                     "kernel": "jot_vocab_reduce_kernel<KL>" if args.kl is not None else "jot_vocab_reduce_kernel",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": ratio * k_bytes if ratio is not None else None,
                      "traffic_per_algorithmic_byte": ratio,
