@@ -467,6 +467,22 @@ def test_config5_full_size_stability_rule_first_steps(gpu):
     run_parity(gpu, CONFIGS[5], batch_rows=[17, 44], max_steps=4, kl=(0.002, 0.0))
 
 
+def test_config4_full_size_blockwise_stability_rule(gpu):
+    # the bf16 two-tensor reduction in its real launch shape, block-wise: positions of a block that
+    # has just become current have no history
+    run_parity(gpu, CONFIGS[4], batch_rows=[0, 13, 31], max_steps=48, kl=KL_CASES[4])
+
+
+def test_config3_full_size_stability_rule(gpu):
+    run_parity(gpu, CONFIGS[3], max_steps=16, kl=KL_CASES[3])
+
+
+def test_config5_full_size_schedule_and_sampling_first_steps(gpu):
+    cfg = CONFIGS[5]
+    run_parity(gpu, cfg, batch_rows=[5, 40], max_steps=3, sample=True,
+               schedule=lambda n: (np.full(cfg.B, 4, np.int32), 0.01))
+
+
 # --------------------------------------------------------------------------- compact logits
 
 def test_config2_compact_logits_with_schedule_and_sampling(gpu):
