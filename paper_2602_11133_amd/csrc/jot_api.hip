@@ -286,13 +286,14 @@ constexpr int kMaxDevices = 64;
 DeviceShape g_shape[kMaxDevices];
 std::mutex g_shape_mutex;
 
-int occupancy_of(const void* kernel, int wg)
+int occupancy_of(const void* kernel, int wg, int cap)
 {
     int occ = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, wg, 0) != hipSuccess || occ < 1) {
         (void)hipGetLastError();
         occ = kDefaultWgPerCu;
     }
+    if (occ > cap) occ = cap;
     return occ > kMaxWgPerCu ? kMaxWgPerCu : occ;
 }
 
@@ -308,11 +309,11 @@ DeviceShape shape_of(int dev)
             cus = kFallbackCus;
         d.cus = cus > 2048 ? 2048 : cus;
         // persistent grids = exactly the workgroups that can be resident at once
-        d.occ[JOT_F32] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotF32>), JotF32::WG);
-        d.occ[JOT_BF16] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotBF16>), JotBF16::WG);
+        d.occ[JOT_F32] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotF32>), JotF32::WG, JotF32::MAX_WG_PER_CU);
+        d.occ[JOT_BF16] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotBF16>), JotBF16::WG, JotBF16::MAX_WG_PER_CU);
         // the reduction with the stability term has its own register footprint, hence its own grid
-        d.occ_kl[JOT_F32] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotF32KL>), JotF32KL::WG);
-        d.occ_kl[JOT_BF16] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotBF16KL>), JotBF16KL::WG);
+        d.occ_kl[JOT_F32] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotF32KL>), JotF32KL::WG, JotF32KL::MAX_WG_PER_CU);
+        d.occ_kl[JOT_BF16] = occupancy_of(reinterpret_cast<const void*>(jot_vocab_reduce_kernel<JotBF16KL>), JotBF16KL::WG, JotBF16KL::MAX_WG_PER_CU);
         d.known = true;
     }
     return d;

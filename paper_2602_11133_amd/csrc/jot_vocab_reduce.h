@@ -32,11 +32,12 @@
 #define JOT_F32_UNROLL 8
 #endif
 #ifndef JOT_BF16_UNROLL
-#define JOT_BF16_UNROLL 4
+#define JOT_BF16_UNROLL 2
 #endif
 // Workgroup sizes of the reduction, chosen by measurement on MI355X: fp32 rows stream best with
 // few, large workgroups (one 1024-thread workgroup per CU, i.e. 256 rows in flight), the bf16
-// path does twice the arithmetic per byte and does best with four 256-thread workgroups per CU.
+// path does twice the arithmetic per byte and does best with four 256-thread workgroups per CU
+// whose threads load the next batch (2 vectors) before they consume the current one.
 #ifndef JOT_F32_WG
 #define JOT_F32_WG 1024
 #endif
@@ -67,6 +68,8 @@ struct JotF32 {
     static constexpr int UNROLL = JOT_F32_UNROLL;   // vectors in flight per thread
     static constexpr int WG = JOT_F32_WG;           // threads per workgroup
     static constexpr bool KL = false;               // also stream the previous step's row
+    static constexpr bool PIPELINED = false;        // loads of batch k+1 issued before batch k is consumed
+    static constexpr int MAX_WG_PER_CU = 16;        // cap on the persistent grid (beyond what fits anyway)
     static constexpr uint32_t NEG_INF_WORD = 0xff800000u;   // one -inf
     __device__ static __forceinline__ void unpack(const jot_u32x4& w, float (&x)[VEC])
     {
@@ -85,6 +88,8 @@ struct JotBF16 {
     static constexpr int UNROLL = JOT_BF16_UNROLL;
     static constexpr int WG = JOT_BF16_WG;
     static constexpr bool KL = false;
+    static constexpr bool PIPELINED = true;         // 2 + 2 vectors in flight: +2-4 % on long bf16 steps
+    static constexpr int MAX_WG_PER_CU = 4;         // more workgroups fit, but more concurrent rows stream slower
     static constexpr uint32_t NEG_INF_WORD = 0xff80ff80u;   // two -inf
     // a bf16 is the upper half of a binary32: widening is a shift / mask, exact
     __device__ static __forceinline__ void unpack(const jot_u32x4& w, float (&x)[VEC])
@@ -109,6 +114,8 @@ struct JotBF16KL : JotBF16 {
     static constexpr int UNROLL = JOT_BF16_KL_UNROLL;
     static constexpr int WG = JOT_BF16_KL_WG;
     static constexpr bool KL = true;
+    static constexpr bool PIPELINED = false;
+    static constexpr int MAX_WG_PER_CU = 16;
 };
 
 // ---- per-lane running state ----------------------------------------------------------------
@@ -285,15 +292,32 @@ __global__ __launch_bounds__(T::WG) void jot_vocab_reduce_kernel(
         JotLane a;
         jot_lane_init(a);
 
-        // Whole batches of U vectors per thread, all loads of a batch issued before any is used.
+        // Whole batches of U vectors per thread, all loads of a batch issued before any is used;
+        // in the pipelined form the loads of the NEXT batch are issued before the current batch
+        // (loaded during the previous iteration) is consumed.
         int base = 0;                                          // workgroup-uniform
+        constexpr bool PIPE = T::PIPELINED && !KL;
+        jot_u32x4 wn[PIPE ? U : 1];
+        if (PIPE && U * WG <= nvec) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) wn[u] = __builtin_nontemporal_load(p + tid + u * WG);
+        }
         for (; base + U * WG <= nvec; base += U * WG) {
             const int c = base + tid;
             jot_u32x4 w[U], wp[KL ? U : 1];
+            if (PIPE) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                w[u] = __builtin_nontemporal_load(p + c + u * WG);
-                if (KL) wp[u] = __builtin_nontemporal_load(pp + c + u * WG);
+                for (int u = 0; u < U; ++u) w[u] = wn[u];
+                if (base + 2 * U * WG <= nvec) {               // workgroup-uniform
+#pragma unroll
+                    for (int u = 0; u < U; ++u) wn[u] = __builtin_nontemporal_load(p + c + U * WG + u * WG);
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    w[u] = __builtin_nontemporal_load(p + c + u * WG);
+                    if (KL) wp[u] = __builtin_nontemporal_load(pp + c + u * WG);
+                }
             }
             float x[U][VEC];
 #pragma unroll
