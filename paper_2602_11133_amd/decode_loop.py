@@ -55,6 +55,49 @@ def decode(state: int, logits_fn, max_steps: int, *, schedule=linear_schedule, n
     return {"steps": steps, "examined_per_step": examined, "still_masked": n_active}
 
 
+def decode_overlapped(state: int, forward_fn, max_steps: int, *, schedule=linear_schedule, n_transfer_dev: int = 0,
+                      stream: int = 0) -> dict:
+    """The same loop with the host's loop test taken off the critical path.  `forward_fn(step)`
+    ENQUEUES the denoiser for `step` on `stream` -- it reads the canvas on the device
+    (jot_tokens / jot_masked) and needs nothing from the host -- and returns (device pointer,
+    stride_b, stride_l) of the logits it will have written.  After enqueueing the finalization
+    pass of step n the loop enqueues the forward pass of step n + 1 straight away and only then
+    looks, without blocking (jot_active_count_poll), whether step n left anything masked: the GPU
+    never waits for the host between steps.  If nothing was left, that last forward pass was
+    speculative work the GPU did for nothing; the canvas is the same as decode()'s."""
+    examined = []
+    n_active = J.jot_active_count(state)
+    steps = 0
+    if n_active == 0 or max_steps < 1:
+        return {"steps": 0, "examined_per_step": examined, "still_masked": n_active, "speculative_forwards": 0}
+    ptr, stride_b, stride_l = forward_fn(1)
+    wasted = 0
+    while True:
+        step = steps + 1
+        opt = J.JotStepOptions()
+        opt.transfer_frac = float(schedule(step, max_steps)) if schedule else 0.0
+        opt.n_transfer_dev = n_transfer_dev or None
+        J.jot_step_ex(state, ptr, stride_b, stride_l, opt, stream)
+        examined.append(n_active)
+        steps = step
+        if step == max_steps:
+            n_active = J.jot_active_count(state)
+            break
+        ptr, stride_b, stride_l = forward_fn(step + 1)       # before the host knows whether it is needed
+        deadline = time.perf_counter() + 5.0
+        while True:
+            n_active, done = J.jot_active_count_poll(state)
+            if done >= step:
+                break
+            if time.perf_counter() > deadline:               # e.g. a state whose steps the host cannot count
+                n_active = J.jot_active_count(state)
+                break
+        if n_active == 0:                                    # Algorithm 1's loop test, one forward pass late
+            wasted = 1
+            break
+    return {"steps": steps, "examined_per_step": examined, "still_masked": n_active, "speculative_forwards": wasted}
+
+
 def _synthetic_run(cfg, early_exit: bool, budget: int | None = None) -> dict:
     """One decode of a synthetic workload on cuda:0 (imports the generators of this repository).
     `budget`: the decoder's step budget T; the workload's own `steps` is the span over which its

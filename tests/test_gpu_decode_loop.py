@@ -72,3 +72,44 @@ def test_driver_equals_the_same_calls_made_by_hand(loop):
     np.testing.assert_array_equal(a.commit_log(), b.commit_log())
     a.close()
     b.close()
+
+
+@pytest.mark.parametrize("cid,small", [(2, dict(steps=24, L=64 + 64)), (4, dict(B=3, L=128 + 64, steps=64))])
+def test_overlapped_loop_decodes_the_same_canvas(loop, cid, small):
+    """decode_overlapped enqueues the next forward pass before it polls the loop test; the canvas,
+    the finalization log and the number of steps are those of the blocking loop."""
+    import gpu_harness as G
+    import paper_2602_11133_amd as J
+    from gen.device import DeviceGenerator
+    from gen.trajectory import Trajectory
+    cfg = CONFIGS[cid].replace(**small)
+    traj = Trajectory(cfg)
+    dgen = DeviceGenerator(cfg, traj.target, traj.rival)
+    tokens0, masked0 = traj.initial_canvas()
+    logits = dgen.alloc_logits(poison=True)
+    # a "denoiser" that needs nothing from the host: it writes the rows of every generation position
+    gen_pos = torch.from_numpy(np.flatnonzero(traj.gen).astype(np.int32)).cuda()
+
+    def forward_fn(step):
+        dgen.set_planted(*traj.planted(step))
+        dgen.fill(logits, step, gen_pos.data_ptr(), gen_pos.numel())
+        return logits.data_ptr(), cfg.L * cfg.V, cfg.V
+
+    def logits_fn(step, active_dev, n_active):
+        return forward_fn(step)
+
+    kw = {}
+    if cfg.block_size > 0:
+        nt = torch.ones(cfg.B, dtype=torch.int32, device="cuda")
+        kw = dict(schedule=None, n_transfer_dev=nt.data_ptr())
+    a = G.GpuJot(G.params_of(cfg), tokens0, masked0)
+    out_a = loop.decode(a.h, logits_fn, 2 * cfg.steps, stream=a.stream, **kw)
+    b = G.GpuJot(G.params_of(cfg), tokens0, masked0)
+    out_b = loop.decode_overlapped(b.h, forward_fn, 2 * cfg.steps, stream=b.stream, **kw)
+    assert out_b["steps"] == out_a["steps"] and out_b["still_masked"] == out_a["still_masked"] == 0
+    assert out_b["examined_per_step"] == out_a["examined_per_step"] and out_b["speculative_forwards"] == 1
+    np.testing.assert_array_equal(a.tokens(), b.tokens())
+    np.testing.assert_array_equal(a.commit_log(), b.commit_log())
+    assert J.jot_step_index(b.h) == out_b["steps"]
+    a.close()
+    b.close()
