@@ -60,12 +60,13 @@ struct JotRowCounts {
     int n_com;      // positions of the row finalized in this step
 };
 
-__device__ __forceinline__ JotRowCounts jot_row_count(const JotCompactParams& prm, int32_t step, int b,
-                                                      const uint8_t* masked, const int32_t* commit_step,
-                                                      int32_t* __restrict__ row_block,
-                                                      int32_t* __restrict__ row_n_active,
-                                                      int32_t* __restrict__ row_n_commit, int* lds)
+// The block a row is decoding: the one that holds its lowest still-masked position (0 outside
+// block mode, where no pass over the row is needed).  Contains barriers.
+__device__ __forceinline__ int jot_row_block(const JotCompactParams& prm, int32_t step, int b,
+                                             const uint8_t* masked, const int32_t* commit_step, int* lds)
 {
+    if (prm.block_size <= 0)
+        return 0;
     const int64_t base = (int64_t)b * prm.L;
     int first = 0x7fffffff;
     for (int i = threadIdx.x; i < prm.L; i += JOT_WG) {
@@ -73,9 +74,17 @@ __device__ __forceinline__ JotRowCounts jot_row_count(const JotCompactParams& pr
         if (still) first = min(first, i);
     }
     first = jot_block_reduce_min(first, lds);
-    int blk = 0;
-    if (prm.block_size > 0 && first != 0x7fffffff)
-        blk = jot_floor_div(first - prm.gen_start, prm.block_size);
+    return first != 0x7fffffff ? jot_floor_div(first - prm.gen_start, prm.block_size) : 0;
+}
+
+__device__ __forceinline__ JotRowCounts jot_row_count(const JotCompactParams& prm, int32_t step, int b,
+                                                      const uint8_t* masked, const int32_t* commit_step,
+                                                      int32_t* __restrict__ row_block,
+                                                      int32_t* __restrict__ row_n_active,
+                                                      int32_t* __restrict__ row_n_commit, int* lds)
+{
+    const int64_t base = (int64_t)b * prm.L;
+    const int blk = jot_row_block(prm, step, b, masked, commit_step, lds);
     int n_act = 0, n_com = 0;
     for (int i = threadIdx.x; i < prm.L; i += JOT_WG) {
         const bool was = masked[base + i] != 0;
@@ -126,19 +135,13 @@ struct JotWriteIO {
 // Pass 2 for batch row b, given where its slices start: act_base = examined positions of the rows
 // before it (next step's list), log_base = commit-log entries before its own, blk = its block.
 // Called by every thread of the workgroup (contains barriers); wave_act / wave_com: JOT_WAVES ints.
-// The workgroup that arrives last closes the step.
-__device__ __forceinline__ void jot_row_write(const JotCompactParams& prm, const JotFrame& frame, int creating,
-                                              const JotWriteIO& io, int b, int64_t act_base, int64_t log_base,
-                                              int blk, int* wave_act, int* wave_com)
+// Returns the row's counts (n_act, n_com; the same in every thread).
+__device__ __forceinline__ JotRowCounts jot_row_write(const JotCompactParams& prm, int32_t* __restrict__ active_out,
+                                                      int32_t step, const JotWriteIO& io, int b, int64_t act_base,
+                                                      int64_t log_base, int blk, int* wave_act, int* wave_com)
 {
-    const int half = frame.epoch->parity;
-    const int32_t step = creating ? -1 : frame.epoch->steps_done + 1;
-    const JotCounters* cnt_in = frame.counters[half];
-    JotCounters* cnt_out = frame.counters[half ^ 1];
-    int32_t* __restrict__ active_out = frame.active[half ^ 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t base = (int64_t)b * prm.L;
-    const int64_t n_examined = cnt_in->n_active;
 
     int run_act = 0, run_com = 0;
     for (int c0 = 0; c0 < prm.L; c0 += JOT_WG) {
@@ -180,30 +183,56 @@ __device__ __forceinline__ void jot_row_write(const JotCompactParams& prm, const
         run_com += tot_com;
         __syncthreads();
     }
+    JotRowCounts out;
+    out.blk = blk; out.n_act = run_act; out.n_com = run_com;
+    return out;
+}
+
+// End of a step, called by every thread of every workgroup of the step's last kernel after its
+// row's write pass: `half` / `done` = the half the step read and the number of completed steps
+// once it is closed; n_examined = positions the step examined; the row's list ended at
+// n_active_end, its log entries at n_log_end.  The workgroup of the last row stores the new
+// counters; the workgroup that arrives last closes the step: every other workgroup has finished
+// reading the epoch by then.  It flips the double buffers, counts the step, and stores the new
+// counters straight into pinned host memory (the host reads them after synchronising).
+// A canvas of one row has one workgroup: nothing to count in, nothing of another workgroup's
+// to make visible, and the counters are the values this thread has just stored.
+__device__ __forceinline__ void jot_close_step(const JotCompactParams& prm, const JotFrame& frame, int half,
+                                               int32_t done, const JotWriteIO& io, int b, int64_t n_examined,
+                                               int64_t n_active_end, int64_t n_log_end)
+{
+    JotCounters* cnt_out = frame.counters[half ^ 1];
     if (b == prm.B - 1 && threadIdx.x == 0) {
-        cnt_out->n_active = act_base + run_act;
-        cnt_out->n_log = log_base + run_com;
+        cnt_out->n_active = n_active_end;
+        cnt_out->n_log = n_log_end;
         cnt_out->n_examined = n_examined;
         cnt_out->reserved = 0;
     }
-    // The workgroup that arrives last closes the step: every other workgroup has finished reading
-    // the epoch by then.  It flips the double buffers, counts the step, and stores the new
-    // counters straight into pinned host memory (the host reads them after synchronising).
     __syncthreads();
     if (threadIdx.x == 0) {
-        __threadfence();
-        const uint32_t arrived = atomicAdd(&frame.epoch->rows_done, 1u);
-        if (arrived == (uint32_t)prm.B - 1u) {
+        bool last = true;
+        int64_t n_active_new = n_active_end, n_log_new = n_log_end, n_examined_new = n_examined;
+        if (prm.B > 1) {
             __threadfence();
-            const int32_t done = frame.epoch->steps_done + (creating ? 0 : 1);
+            const uint32_t arrived = atomicAdd(&frame.epoch->rows_done, 1u);
+            last = arrived == (uint32_t)prm.B - 1u;
+            if (last) {
+                __threadfence();
+                // device-scope loads: the numbers were written by the workgroup of the last row
+                n_active_new = __hip_atomic_load(&cnt_out->n_active, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                n_log_new = __hip_atomic_load(&cnt_out->n_log, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                n_examined_new = __hip_atomic_load(&cnt_out->n_examined, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        if (last) {
+            const unsigned long long anomalies = __hip_atomic_load(io.anomalies, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             io.host_out->begin = done;
             __threadfence_system();
-            // device-scope loads: the numbers were written by the workgroup of the last row
-            io.host_out->c.n_active = __hip_atomic_load(&cnt_out->n_active, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            io.host_out->c.n_log = __hip_atomic_load(&cnt_out->n_log, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            io.host_out->c.n_examined = __hip_atomic_load(&cnt_out->n_examined, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            io.host_out->c.n_active = n_active_new;
+            io.host_out->c.n_log = n_log_new;
+            io.host_out->c.n_examined = n_examined_new;
             io.host_out->c.reserved = 0;
-            io.host_out->anomalies = __hip_atomic_load(io.anomalies, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            io.host_out->anomalies = anomalies;
             io.host_out->parity = half ^ 1;
             __threadfence_system();
             io.host_out->steps_done = done;
@@ -211,7 +240,6 @@ __device__ __forceinline__ void jot_row_write(const JotCompactParams& prm, const
             frame.epoch->rows_done = 0u;
             frame.epoch->steps_done = done;
             frame.epoch->parity = half ^ 1;
-            __threadfence_system();
         }
     }
 }
@@ -222,6 +250,9 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
     const int32_t* __restrict__ row_block, const int32_t* __restrict__ row_n_commit)
 {
     const int half = frame.epoch->parity;
+    const int32_t steps_done = frame.epoch->steps_done;
+    const int64_t n_examined = frame.counters[half]->n_active;
+    const int64_t n_log = frame.counters[half]->n_log;
     const int32_t* __restrict__ row_n_active = frame.row_counts[half ^ 1];
     __shared__ int lds[JOT_WAVES];
     __shared__ int wave_act[JOT_WAVES], wave_com[JOT_WAVES];
@@ -232,9 +263,11 @@ __global__ __launch_bounds__(JOT_WG) void jot_row_write_kernel(
         pc += row_n_commit[k];
     }
     const int64_t act_base = jot_block_reduce_sum(pa, lds);
-    const int64_t com_prefix = jot_block_reduce_sum(pc, lds);
-    const int64_t log_base = frame.counters[half]->n_log + com_prefix;
-    jot_row_write(prm, frame, creating, io, b, act_base, log_base, row_block[b], wave_act, wave_com);
+    const int64_t log_base = n_log + jot_block_reduce_sum(pc, lds);
+    const JotRowCounts rc = jot_row_write(prm, frame.active[half ^ 1], creating ? -1 : steps_done + 1, io, b,
+                                          act_base, log_base, row_block[b], wave_act, wave_com);
+    jot_close_step(prm, frame, half, steps_done + (creating ? 0 : 1), io, b, n_examined,
+                   act_base + rc.n_act, log_base + rc.n_com);
 }
 
 // Copy of the caller's initial canvas into the workspace.

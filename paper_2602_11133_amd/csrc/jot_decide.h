@@ -48,8 +48,11 @@ struct JotDecideParams {
 };
 
 // Everything for one examined entry r of the list (pieces = pieces per row this step).
+// row_words: the bit image of the entry's batch row if the caller holds a copy of it (all entries
+// it passes are then of that row), else NULL and the words are read from io.resolved_bits.
 __device__ __forceinline__ void jot_decide_one(const JotDecideParams& prm, const JotDecideIO& io,
-                                               int32_t step, int64_t r, int pieces)
+                                               int32_t step, int64_t r, int pieces,
+                                               const uint64_t* row_words = nullptr)
 {
     // ---- merge the pieces of the row, in piece order: S_raw = sum_v exp(l_v - m1), cross on the same scale
     float m1, m2, S_raw, cross;
@@ -78,7 +81,7 @@ __device__ __forceinline__ void jot_decide_one(const JotDecideParams& prm, const
     const int i = pos - b * prm.L;
     float phi = 0.0f;
     if (prm.D > 0) {
-        const uint64_t* words = io.resolved_bits + (int64_t)b * prm.words_per_row;
+        const uint64_t* words = row_words ? row_words : io.resolved_bits + (int64_t)b * prm.words_per_row;
         const int wi = i >> 6, bi = i & 63;
         const uint64_t mid = words[wi];
         const uint64_t lo = wi > 0 ? words[wi - 1] : 0ull;

@@ -80,6 +80,30 @@ struct JotFrame {
     int32_t* row_counts[2];     // per batch row: examined positions of that row
 };
 
+// What a kernel needs to know about the running step.  The counters of BOTH halves are requested
+// together with the epoch that says which half counts, so a kernel that starts on cold caches
+// waits for one memory round trip here, not two.  For kernels that do not write the counters
+// before every workgroup has read them.
+struct JotNow {
+    int half;           // half of the double buffers the running step reads
+    int32_t step;       // number of the running step
+    int64_t n_active;   // positions it examines
+    int64_t n_log;      // commit-log triples written before it
+};
+
+__device__ __forceinline__ JotNow jot_now(const JotFrame& f)
+{
+    const int32_t parity = f.epoch->parity, done = f.epoch->steps_done;
+    const int64_t a0 = f.counters[0]->n_active, a1 = f.counters[1]->n_active;
+    const int64_t l0 = f.counters[0]->n_log, l1 = f.counters[1]->n_log;
+    JotNow n;
+    n.half = parity;
+    n.step = done + 1;
+    n.n_active = parity ? a1 : a0;
+    n.n_log = parity ? l1 : l0;
+    return n;
+}
+
 // Block the last compaction workgroup writes into host-visible pinned memory.
 // Written in the order: begin, (fence), everything else, (fence), steps_done -- so a host reader
 // that finds begin == steps_done around its reads has a consistent snapshot of that step.

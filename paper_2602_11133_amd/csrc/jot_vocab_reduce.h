@@ -262,9 +262,9 @@ __global__ __launch_bounds__(T::WG) void jot_vocab_reduce_kernel(
     constexpr int WG = T::WG;
     constexpr int WAVES = WG / 64;
     constexpr bool KL = T::KL;
-    const int half = frame.epoch->parity;
-    const int32_t* __restrict__ active = frame.active[half];
-    const int64_t n_active = frame.counters[half]->n_active;
+    const JotNow now = jot_now(frame);
+    const int32_t* __restrict__ active = frame.active[now.half];
+    const int64_t n_active = now.n_active;
     const JotSplit sp = jot_plan_split(n_active, V, target_items, WG * VEC * U);
     const int64_t n_items = n_active * sp.S;
     const int tid = threadIdx.x;
