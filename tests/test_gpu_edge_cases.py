@@ -189,6 +189,17 @@ def test_block_mode(gpu, block):
     check_case(gpu, p, tokens, masked, seq)
 
 
+@pytest.mark.parametrize("block", [0, 1, 32, 500])
+def test_single_row_canvas_longer_than_a_workgroup(gpu, block):
+    # one batch row: decisions, compaction and the closing of the step run in one workgroup of one
+    # launch, which walks the row in several chunks and, in block mode, looks for the block first
+    say(f"[edge] single row, block={block}")
+    p, tokens, masked, seq = random_case(40 + block, B=1, L=700, V=300, gs=45, conf_mode=O.CONF_MAXPROB,
+                                         tau_max=0.7, tau_min=0.0, gamma=0.5, D=8, block_size=block, steps=8)
+    masked[0, 10:20] = True          # masked positions inside the prompt region too
+    check_case(gpu, p, tokens, masked, seq)
+
+
 def test_rows_split_into_pieces_with_ties_across_pieces(gpu):
     # few examined rows and a long vocabulary: each row is cut into several pieces that are
     # merged afterwards; equal maxima sit in different pieces
