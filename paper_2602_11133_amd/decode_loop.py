@@ -98,8 +98,11 @@ def decode_overlapped(state: int, forward_fn, max_steps: int, *, schedule=linear
     return {"steps": steps, "examined_per_step": examined, "still_masked": n_active, "speculative_forwards": wasted}
 
 
-def _synthetic_run(cfg, early_exit: bool, budget: int | None = None) -> dict:
+def _synthetic_run(cfg, early_exit: bool, budget: int | None = None, overlapped: bool | None = None) -> dict:
     """One decode of a synthetic workload on cuda:0 (imports the generators of this repository).
+    `overlapped`: None = decode() with a stand-in denoiser that writes the rows of the examined
+    positions only; False / True = decode() / decode_overlapped() with one that writes the rows of
+    every generation position and so needs nothing from the host (the same work in both).
     `budget`: the decoder's step budget T; the workload's own `steps` is the span over which its
     planted tokens converge, so a budget above it models a decoder configured with more steps
     than the sequence needs."""
@@ -137,8 +140,21 @@ def _synthetic_run(cfg, early_exit: bool, budget: int | None = None) -> dict:
         per_step = -(-cfg.block_size // max(1, budget // n_blocks))
         nt = torch.full((cfg.B,), per_step, dtype=torch.int32, device="cuda:0")
         kw = dict(schedule=None, n_transfer_dev=nt.data_ptr())
+    gen_list = torch.from_numpy(np.flatnonzero(traj.gen).astype(np.int32)).cuda()
+
+    def forward_fn(step):
+        T, R = traj.planted(step)
+        dgen.set_planted(T, R)
+        dgen.fill(logits, step, gen_list.data_ptr(), gen_list.numel())
+        return logits.data_ptr(), cfg.L * cfg.V, cfg.V
+
     t0 = time.perf_counter()
-    out = decode(h, logits_fn, budget, stream=stream, **kw)
+    if overlapped:
+        out = decode_overlapped(h, forward_fn, budget, stream=stream, **kw)
+    elif overlapped is not None:
+        out = decode(h, lambda step, active_dev, n_active: forward_fn(step), budget, stream=stream, **kw)
+    else:
+        out = decode(h, logits_fn, budget, stream=stream, **kw)
     torch.cuda.synchronize()
     out["seconds_including_the_input_generator"] = time.perf_counter() - t0
     final = J.device_to_host(J.jot_tokens(h), cfg.B * cfg.L, np.int32)
@@ -156,6 +172,8 @@ def main() -> None:
                     help="steps over which the workload's planted tokens converge (default: the workload's)")
     ap.add_argument("--budget", type=int, default=None, help="the decoder's step budget T (default: twice --steps)")
     ap.add_argument("--batch", type=int, default=None, help="override the batch size")
+    ap.add_argument("--overlapped", action="store_true",
+                    help="also time the loop that enqueues the next forward pass before it tests the last step")
     args = ap.parse_args()
     cfg = CONFIGS[args.config]
     if args.steps:
@@ -165,7 +183,15 @@ def main() -> None:
     budget = args.budget or 2 * cfg.steps
     fixed = _synthetic_run(cfg, early_exit=False, budget=budget)
     early = _synthetic_run(cfg, early_exit=True, budget=budget)
+    extra = {}
+    if args.overlapped:
+        again = _synthetic_run(cfg, early_exit=True, budget=budget, overlapped=False)   # both timed on warm code paths
+        over = _synthetic_run(cfg, early_exit=True, budget=budget, overlapped=True)
+        extra = {"us_per_step_blocking_loop": 1e6 * again["seconds_including_the_input_generator"] / again["steps"],
+                 "us_per_step_overlapped_loop": 1e6 * over["seconds_including_the_input_generator"] / over["steps"],
+                 "steps_overlapped_loop": over["steps"]}
     print(json.dumps({
+        **extra,
         "workload": cfg.name, "B": cfg.B, "generated_positions": cfg.n_gen, "V": cfg.V, "convergence_span": cfg.steps, "step_budget": budget,
         "steps_schedule_only": fixed["steps"], "steps_with_early_exit": early["steps"],
         "step_reduction": fixed["steps"] / max(1, early["steps"]),
