@@ -87,7 +87,19 @@ int main(int argc, char **argv)
         CHECK_HIP(hipMemcpy2DAsync(logits_dev, stride_l * esz, lg, (size_t)p.V * esz, (size_t)p.V * esz, n,
                                    hipMemcpyHostToDevice, stream));
         CHECK_JOT(jot_step(st, logits_dev, (int64_t)(p.L * stride_l), (int64_t)stride_l, stream));
+        /* the non-blocking form: poll until the step has closed, then the blocking call must agree */
+        int64_t polled = -1;
+        for (long spins = 0; spins < 200000000L; spins++) {
+            int32_t done = -1;
+            polled = jot_active_count_poll(st, &done);
+            if (polled < 0) { fprintf(stderr, "poll failed: %s\n", jot_strerror((int)polled)); return 6; }
+            if (done >= steps_run + 1)
+                break;
+            polled = -1;
+        }
         counts[steps_run++] = jot_active_count(st);  /* also makes it safe to free the host copy */
+        if (polled != counts[steps_run - 1]) { fprintf(stderr, "polled count %lld differs from %lld\n",
+                                                      (long long)polled, (long long)counts[steps_run - 1]); return 6; }
         free(lg);
     }
     if (jot_step_index(st) != steps_run) { fprintf(stderr, "step index mismatch\n"); return 5; }
