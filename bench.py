@@ -39,7 +39,8 @@ FLUSH_BYTES = 1 << 30
 # for the kernel sources with these hashes and for these workloads and logit types; otherwise
 # bench.py reports null.
 MEASURED_TRAFFIC = {
-    "hbm_bytes_per_algorithmic_byte": {(5, "f32"): 1.00060, (5, "bf16"): 1.00088, (3, "bf16"): 1.00085},
+    "hbm_bytes_per_algorithmic_byte": {(5, "f32"): 1.00060, (5, "bf16"): 1.00088, (3, "bf16"): 1.00085,
+                                       (4, "bf16"): 1.00137, (2, "bf16"): 1.00311},
     "sha256": {"jot_vocab_reduce.h": "ec222316785395e737ad2d6907c8b24e1746203b62f883bb672246bb4554231d",
                "jot_device.h": "d4fb409aab4572866a739d578d94a361c1d9edb11176acebcc835d57ae63b89c"},
 }
