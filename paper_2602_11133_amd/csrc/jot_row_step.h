@@ -1,10 +1,10 @@
 // Per-row step kernel: for canvases whose rows examine at most a couple of thousand positions
 // per step (every workload of the paper's shape) the decision (Eq. 2 - Eq. 6), the optional
-// transfer schedule, the optional row-wide early commit and the per-row counting pass of the compaction run in ONE launch, one
-// workgroup per batch row, instead of three.  Nothing crosses rows here: a row's slice of the
-// examined list is found from the per-row counts of the previous step, and the counts for the
-// next step go to the other half of a double buffer (a workgroup that starts late must still
-// see the old counts of the rows before it).
+// transfer schedule, the optional row-wide early commit and the per-row counting pass of the
+// compaction run in ONE launch, one workgroup per batch row, instead of three.  Nothing crosses
+// rows here: a row's slice of the examined list is found from the per-row counts of the
+// previous step, and the counts for the next step go to the other half of a double buffer (a
+// workgroup that starts late must still see the old counts of the rows before it).
 #pragma once
 #include "jot_compact.h"
 #include "jot_decide.h"
@@ -12,7 +12,6 @@
 
 #define JOT_ROW_WORDS_LDS 512              // rows of up to 32 768 positions keep their bit image in LDS
 
-//
 // With a single batch row (the setting of the paper's experiments) nothing is left for a second
 // launch to wait for, and the same workgroup goes on to the write pass of the compaction
 // (`write_too`; the host asks for it only when B == 1 and the step does not sample its tokens,
