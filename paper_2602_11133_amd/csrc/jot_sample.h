@@ -11,9 +11,10 @@
 //
 // One workgroup per finalized row.  The exponentials are binary32 (v_exp_f32), every sum is
 // accumulated in double, and the threshold u * S uses the kernel's own total S of the same
-// terms, so the cumulative probabilities are good to about 1e-7.  Three sweeps: (1) the total S;
-// (2) the same batch totals again, stopping at the batch whose running total first exceeds
-// u * S (bitwise the same numbers as in sweep 1); (3) inside that batch, an ordered inclusive
+// terms, so the cumulative probabilities are good to about 1e-7.  Three steps: (1) the total S,
+// batch by batch; (2) the batch whose running total first exceeds u * S, from the batch totals
+// kept in LDS (rows of more than JOT_SAMPLE_KEPT batches are swept a second time instead, which
+// gives bitwise the same totals); (3) inside that batch, an ordered inclusive
 // scan over the 16-byte vectors (wave shuffles + LDS offsets) finds the vector, and its owner
 // walks the vector's elements.  All running totals are workgroup-uniform, so every branch on
 // them is uniform.  If the cumulative sum never exceeds u * S (u within rounding of 1, or a
@@ -22,6 +23,8 @@
 #pragma once
 #include "jot_device.h"
 #include "jot_vocab_reduce.h"
+
+#define JOT_SAMPLE_KEPT 64             // batch totals of a row kept in LDS: rows of up to 524 288 elements
 
 template <class T>
 struct JotSampleShape {
@@ -55,6 +58,7 @@ __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
     constexpr int BATCH_VEC = JotSampleShape<T>::BATCH_VEC;
     __shared__ double lds[JOT_WAVES];
     __shared__ double wave_tot[JOT_WAVES];
+    __shared__ double kept[JOT_SAMPLE_KEPT];
     __shared__ int found_token;
     const int32_t* __restrict__ active = frame.active[frame.epoch->parity];
     const int n_items = *sample_count;            // rows finalized this step, listed by the kernels before
@@ -94,18 +98,24 @@ __global__ __launch_bounds__(JOT_WG) void jot_sample_kernel(
             return (double)__builtin_amdgcn_exp2f((T::scalar(row, v) - top) * JOT_LOG2E);
         };
 
-        // (1) total
+        // (1) total; the batch totals are kept if the row has few enough batches
+        const bool keep = (nvec + BATCH_VEC - 1) / BATCH_VEC <= JOT_SAMPLE_KEPT;
         double S = 0.0;
-        for (int base = 0; base < nvec; base += BATCH_VEC) S += batch_total(base);
+        for (int base = 0, k = 0; base < nvec; base += BATCH_VEC, ++k) {
+            const double total = batch_total(base);
+            if (keep && tid == 0) kept[k] = total;
+            S += total;
+        }
         for (int v = nvec * VEC; v < V; ++v) S += tail_term(v);
+        __syncthreads();                                          // kept[] is complete
         const float u01 = uniforms[pos];
         const double thresh = (u01 < 1.0f) ? (double)u01 * S : (double)INFINITY;   // u >= 1: nothing exceeds it
 
         // (2) the batch in which the running total first exceeds thresh
         double running = 0.0;
         int cross = -1;
-        for (int base = 0; base < nvec; base += BATCH_VEC) {
-            const double total = batch_total(base);
+        for (int base = 0, k = 0; base < nvec; base += BATCH_VEC, ++k) {
+            const double total = keep ? kept[k] : batch_total(base);
             if (running + total > thresh) {
                 cross = base;
                 break;

@@ -347,7 +347,7 @@ def test_schedule_on_a_long_row(gpu):
 # --------------------------------------------------------------------------- sampling-based finalization
 
 @pytest.mark.parametrize("dtype", [O.F32, O.BF16])
-@pytest.mark.parametrize("V", [2, 9, 1003, 8192, 8200, 40_003])
+@pytest.mark.parametrize("V", [2, 9, 1003, 8192, 8200, 40_003, 600_001])     # the last: more batches than the kernel keeps totals of
 def test_sampled_tokens(gpu, dtype, V):
     say(f"[edge] sampling V={V} dtype={dtype}")
     # flat-ish rows (scale 1.5) so that samples differ from the argmax; tau = 0: everything is finalized
