@@ -5,9 +5,9 @@
 //
 // One workgroup per batch row.  Among the positions the row examined this step it selects the
 // k with the largest p1 (equal p1: lower position first) and finalizes those that Eq. 6 has not
-// finalized already.  Selection is exact and order-deterministic: a bitwise radix descent over
-// the binary32 patterns of p1 (positive floats order like unsigned integers) finds the k-th
-// largest value T with wave ballots and popcounts; everything above T is taken, and of the
+// finalized already.  Selection is exact and order-deterministic: a radix descent over the
+// binary32 patterns of p1 (positive floats order like unsigned integers), one byte per pass,
+// finds the k-th largest value T from histograms in LDS; everything above T is taken, and of the
 // values equal to T the first k - #(> T) in position order, by a ballot prefix scan.
 #pragma once
 #include "jot_device.h"
@@ -98,18 +98,62 @@ __device__ __forceinline__ void jot_schedule_row(const JotScheduleParams& prm, c
         return;
     const int k = (int)want;
 
-    // T = k-th largest key: the largest value with #(key >= T) >= k, built bit by bit.
+    // T = k-th largest key, one byte of it per pass, most significant first: a histogram of that
+    // byte over the keys that agree with the bytes fixed so far (LDS atomics; counts do not depend
+    // on their order), suffix sums over the 256 bins, and the bin in which the k-th largest lies.
+    // need_eq = how many of the keys equal to T are still to be taken after everything above it.
     // When everything with a softmax is taken, T stays 0 (all their keys are >= 1 > T).
+    static_assert(JOT_WG == 256, "one histogram bin per thread");
     uint32_t T = 0u;
+    int need_eq = 0;
     if (k < n_valid) {
-        for (int bit = 30; bit >= 0; --bit) {          // keys are positive floats: bit 31 is clear
-            const uint32_t cand = T | (1u << bit);
-            if (count_ge(cand) >= k)
-                T = cand;
+        __shared__ int hist[256];
+        __shared__ int wave_sum[JOT_WAVES];
+        __shared__ int pick[2];                         // the chosen bin, and the keys in the bins above it
+        uint32_t fixed = 0u;                            // mask of the bytes of T fixed so far
+        int k_rem = k;                                  // rank of T among the keys that agree with them
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            hist[threadIdx.x] = 0;
+            __syncthreads();
+            auto count = [&](uint32_t key) {
+                if (key != 0u && (key & fixed) == T)
+                    atomicAdd(&hist[(key >> shift) & 255u], 1);
+            };
+            if (cached) {
+#pragma unroll
+                for (int q = 0; q < CACHE; ++q)
+                    if (q * JOT_WG < n) count(kreg[q]);
+            } else {
+                for (int j = threadIdx.x; j < n; j += JOT_WG) count(load_key(j));
+            }
+            __syncthreads();
+            // keys in bins >= t: suffix sum inside the wave, then the waves above
+            const int h = hist[threadIdx.x];
+            int s = h;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int v = __shfl_down(s, off, 64);
+                if (lane + off < 64) s += v;
+            }
+            if (lane == 0) wave_sum[wave] = s;
+            __syncthreads();
+            int higher = 0;
+#pragma unroll
+            for (int w = 0; w < JOT_WAVES; ++w)
+                if (w > wave) higher += wave_sum[w];
+            const int at_least = s + higher, above_bin = at_least - h;
+            if (at_least >= k_rem && above_bin < k_rem) {     // exactly one bin
+                pick[0] = threadIdx.x;
+                pick[1] = above_bin;
+            }
+            __syncthreads();
+            T |= (uint32_t)pick[0] << shift;
+            fixed |= 255u << shift;
+            k_rem -= pick[1];
+            __syncthreads();                            // before the bins and the pick are written again
         }
+        need_eq = k_rem;
     }
-    const int n_above = (T == 0xffffffffu) ? 0 : count_ge(T + 1u);
-    const int need_eq = k - n_above;   // entries equal to T still to take (0 when taking all)
 
     // take: key > T, and the first need_eq entries with key == T
     int run_eq = 0;
